@@ -1,0 +1,207 @@
+/*
+ * wap.h -- C ABI of the MI355X (gfx950) per-replica training-step kernels.
+ *
+ * The library implements the compute side of one data-parallel replica (Section 2.1): the
+ * forward and backward processing of every layer, i.e. the t_c(l_i, d) term of the run-time
+ * estimate of Eq. 1 (Section 3.2.1), for the layer types the paper's parser extracts --
+ * convolution and fully-connected "primary" nodes plus the activation / loss "auxiliary"
+ * nodes (Section 3.2.2) and the weight update that follows gradient aggregation
+ * (Section 3.2.3) -- and the measured per-layer time / utilisation table versus per-GPU
+ * minibatch that the workload analysis unit evaluates Eq. 1 over.
+ *
+ * Conventions (all entry points):
+ *   - extern "C"; return a wap_status; never throw, never abort.
+ *   - Every tensor pointer is DEVICE memory owned by the caller, 16-byte aligned, and must stay
+ *     alive until the work enqueued on `stream` has finished.  The library keeps no reference
+ *     after return, allocates and frees no device memory and (except wap_profile_layer and the
+ *     step-plan timing helper) never synchronises.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *   - bf16 tensors are arrays of 16-bit bfloat16 bit patterns.  Accumulation is fp32.
+ *     Conversions to bf16 round to nearest, ties to even.
+ *   - Layouts: activations x[N][H][W][C] and y[N][P][Q][K]; conv weights w[K][R][S][C];
+ *     FC weights Wt[out][in]; all row-major and dense.  P = floor((H + 2*pad_h - R)/stride_h) + 1.
+ *   - Outputs are fully overwritten (no accumulate-into semantics).
+ *   - Arguments are validated on the host before any device work: WAP_EINVAL for null
+ *     pointers, non-positive sizes, pad >= filter size, misalignment; WAP_EUNSUPPORTED for
+ *     sizes whose element counts exceed 2^31-1; WAP_EWORKSPACE when `ws_bytes` is below the
+ *     matching *_workspace_bytes query; WAP_EHIP when a launch fails.  wap_last_error() gives
+ *     the text of the last failure on the calling thread.
+ *   - `ws` is scratch the caller provides (device memory, 256-byte aligned); it holds split
+ *     reduction partials and may be NULL when the query returns 0.
+ */
+#ifndef WAP_H
+#define WAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WAP_OK = 0,
+    WAP_EINVAL = 1,
+    WAP_EUNSUPPORTED = 2,
+    WAP_EWORKSPACE = 3,
+    WAP_EHIP = 4
+} wap_status;
+
+/* flags */
+#define WAP_RELU 1u /* forward epilogue applies max(.,0) after the optional bias */
+
+/* One convolution layer's workload record (what the neural-net parser of Section 3.2.2
+ * extracts: layer shape including the minibatch N).  Dilation 1, one group. */
+typedef struct {
+    int32_t N, H, W, C;       /* input  x[N][H][W][C] */
+    int32_t K, R, S;          /* filter w[K][R][S][C] */
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;
+    uint32_t flags;           /* WAP_RELU */
+} wap_conv_desc;
+
+/* One fully-connected layer's workload record: y[B][out] = x[B][in] * Wt[out][in]^T. */
+typedef struct {
+    int32_t B, in_features, out_features;
+    uint32_t flags;           /* WAP_RELU */
+} wap_fc_desc;
+
+typedef enum { WAP_PASS_FWD = 0, WAP_PASS_BWD_DATA = 1, WAP_PASS_BWD_WEIGHT = 2 } wap_pass;
+
+int wap_version(void);
+const char* wap_last_error(void);
+
+/* Testing aid (process-wide, not thread safe): force the tile configuration of the forward-type
+ * kernels (0..3), of the weight-gradient kernel (0..2) and the number of reduction splits; -1
+ * restores the shape-driven choice.  Forced values that the shape cannot use are ignored, and the
+ * *_workspace_bytes queries reflect the forced choice. */
+void wap_debug_force(int fwd_cfg, int wgrad_cfg, int nsplit);
+
+/* ---- convolution (primary node, Section 3.2.2; forward and backward halves of t_c, Eq. 1) ---- */
+
+/* Scratch bytes the given pass needs for this descriptor (0 is possible). */
+int wap_conv2d_workspace_bytes(const wap_conv_desc* d, int pass, size_t* bytes_out);
+
+/* y[n,p,q,k] = act( bias[k] + sum_{r,s,c} x[n, p*stride_h-pad_h+r, q*stride_w-pad_w+s, c] * w[k,r,s,c] ),
+ * taps outside the image contribute zero.  x, w, y: bf16 device; bias: fp32 device [K] or NULL. */
+int wap_conv2d_fwd(const wap_conv_desc* d, const void* x, const void* w, const float* bias,
+                   void* y, void* ws, size_t ws_bytes, void* stream);
+
+/* dx[n,h,w,c] = sum_{k,r,s} dy[n,p,q,k] * w[k,r,s,c] over the (p,q) whose tap (r,s) reads (h,w).
+ * dy: bf16 [N][P][Q][K]; dx: bf16 [N][H][W][C], every element written (zeros where the forward
+ * pass never reads). */
+int wap_conv2d_bwd_data(const wap_conv_desc* d, const void* dy, const void* w, void* dx,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride_h-pad_h+r, q*stride_w-pad_w+s, c].
+ * dw: fp32 [K][R][S][C] (the tensor a gradient all-reduce would move, Section 3.2.3).
+ * The split reduction is summed in a fixed order: results are bitwise reproducible. */
+int wap_conv2d_bwd_weight(const wap_conv_desc* d, const void* x, const void* dy, float* dw,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/* ---- fully connected (primary node, Section 3.2.2) ---- */
+int wap_fc_workspace_bytes(const wap_fc_desc* d, int pass, size_t* bytes_out);
+
+/* y[b,o] = act( bias[o] + sum_i x[b,i] * Wt[o,i] );  x bf16 [B][in], Wt bf16 [out][in], y bf16 [B][out]. */
+int wap_fc_fwd(const wap_fc_desc* d, const void* x, const void* Wt, const float* bias,
+               void* y, void* ws, size_t ws_bytes, void* stream);
+
+/* dx[b,i] = sum_o dy[b,o] * Wt[o,i] (bf16, skipped when dx is NULL);
+ * dW[o,i] = sum_b dy[b,o] * x[b,i]  (fp32, skipped when dW is NULL).  dy bf16 [B][out].
+ * `ws` must satisfy the larger of the BWD_DATA and BWD_WEIGHT queries. */
+int wap_fc_bwd(const wap_fc_desc* d, const void* x, const void* Wt, const void* dy,
+               void* dx, float* dW, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- auxiliary nodes (activation, pooling, loss: Section 3.2.2) and the weight update
+ *      (Section 3.2.3).  The paper names them without formulas; the definitions are the
+ *      standard ones, with the tie and zero-point rules stated here. ---- */
+
+/* dx[i] = y[i] > 0 ? dy[i] : 0  (derivative at zero is zero).  bf16, n elements; dx may alias dy. */
+int wap_relu_bwd(const void* dy, const void* y, void* dx, int64_t n, void* stream);
+
+/* Max-pool, square window `win` (2 or 3), stride `st`, no padding, floor output size.
+ * y bf16 [N][P][Q][C]; argmax uint8 [N][P][Q][C] = r*win+s of the FIRST maximum in (r, s) scan order. */
+int wap_maxpool_fwd(int32_t N, int32_t H, int32_t W, int32_t C, int32_t win, int32_t st,
+                    const void* x, void* y, uint8_t* argmax, void* stream);
+
+/* dx[n,h,w,c] = sum of dy over the windows whose argmax is (h,w); every dx element written.
+ * If relu_y is not NULL it is the pooled forward output y (bf16): contributions of windows with
+ * y <= 0 are dropped, which fuses the backward of a ReLU placed just before the pool. */
+int wap_maxpool_bwd(int32_t N, int32_t H, int32_t W, int32_t C, int32_t win, int32_t st,
+                    const void* dy, const uint8_t* argmax, const void* relu_y, void* dx, void* stream);
+
+/* Softmax cross-entropy, mean over the minibatch: p = softmax(z[b,:]) in fp32,
+ * row_loss[b] = -log p[b,label_b] (fp32 [B]), loss = (1/B) sum_b row_loss[b] (one fp32 on device,
+ * fixed summation order), dz[b,j] = (p[b,j] - [j == label_b]) / B stored bf16.
+ * z bf16 [B][classes]; labels int32 [B], each in [0, classes) (not checked on the device). */
+int wap_softmax_xent_grad(int32_t B, int32_t classes, const void* z, const int32_t* labels,
+                          float* loss, float* row_loss, void* dz, void* stream);
+
+/* Plain SGD on fp32 master weights: w32 <- w32 - lr*dw (fp32), then w_bf16 <- bf16(w32).
+ * n elements; w_bf16 may be NULL. */
+int wap_sgd_update(int64_t n, float* w32, const float* dw, float lr, void* w_bf16, void* stream);
+
+/* fp32 -> bf16 copy of n elements (used to derive the compute copy of freshly set master weights). */
+int wap_cast_f32_bf16(int64_t n, const float* src, void* dst, void* stream);
+
+/* ---- the per-layer time / utilisation table (the t_c(l_i, d) entries of Eq. 1 that the
+ *      workload analysis unit of Section 3.2.1 sums and minimises over d) ---- */
+typedef struct {
+    int32_t pass;              /* wap_pass */
+    int32_t minibatch;         /* per-GPU minibatch this row was timed at */
+    double flops;              /* algorithmic: 2*N*P*Q*K*C*R*S (padding taps included) or 2*B*in*out */
+    double alg_bytes;          /* every operand read once + output written once */
+    double time_us_median;
+    double time_us_min;
+    double tflops;             /* flops / median time */
+    double frac_of_bf16_peak;  /* against 2516.6 TFLOP/s */
+    double gbytes_per_s;       /* alg_bytes / median time */
+    double frac_of_hbm_peak;   /* against 8000 GB/s */
+    int32_t bound;             /* 0 = MFMA side of the ridge, 1 = HBM side */
+    int32_t reserved;
+} wap_profile_row;
+
+/* Device scratch needed to profile the layer at every listed minibatch (inputs, outputs, workspace). */
+int wap_profile_scratch_bytes(int kind /*0 conv, 1 fc*/, const void* desc, const int32_t* minibatches,
+                              int32_t n_mb, size_t* bytes_out);
+
+/* Times fwd, bwd-data and bwd-weight of one layer at each minibatch in `minibatches`
+ * (the descriptor's N / B is replaced by the minibatch) with HIP events on `stream`:
+ * `warmup` untimed launches then `iters` timed ones per row.  Writes 3*n_mb rows (pass-major
+ * within each minibatch).  Scratch contents are filled with a fixed pattern; this call
+ * synchronises the stream. */
+int wap_profile_layer(int kind, const void* desc, const int32_t* minibatches, int32_t n_mb,
+                      int32_t warmup, int32_t iters, void* scratch, size_t scratch_bytes,
+                      void* stream, wap_profile_row* rows_out, int32_t rows_cap, int32_t* rows_written);
+
+/* ---- whole training step of one replica: forward, loss, backward, SGD (host-side launch list) ---- */
+typedef struct wap_step_plan wap_step_plan;
+
+/* net: "alexnet" or "vgg16" (layer lists of Section 4.1's two networks, 224x224x3 inputs,
+ * 1000 classes, no bias).  The plan is host memory only. */
+int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, float lr, uint32_t flags,
+                         wap_step_plan** out);
+void wap_step_plan_destroy(wap_step_plan* p);
+/* Bytes of the single device arena the step runs in (weights, activations, gradients, workspace). */
+int wap_step_arena_bytes(const wap_step_plan* p, size_t* bytes_out);
+/* Number of named tensors in the arena and their placement; names are e.g. "conv1_1.w32",
+ * "conv1_1.w", "conv1_1.y", "pool1.y", "fc6.dW", "input", "labels", "loss". */
+int wap_step_num_tensors(const wap_step_plan* p);
+int wap_step_tensor(const wap_step_plan* p, int32_t index, const char** name, size_t* offset,
+                    size_t* bytes);
+/* Enqueues one full step on `stream`: no allocation, no synchronisation. */
+int wap_step_run(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream);
+/* Algorithmic FLOPs of one step (direct-convolution count, first layer's data gradient excluded). */
+double wap_step_flops(const wap_step_plan* p);
+/* Number of operations in the launch list (an operation is one kernel, or a kernel plus its
+ * split-reduction epilogue). */
+int wap_step_num_ops(const wap_step_plan* p);
+/* Runs the step once with a HIP event pair around every operation; fills us_out[num_ops] and
+ * names_out[num_ops] (strings owned by the plan, e.g. "conv3_2.wgrad").  Synchronises. */
+int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream,
+                  float* us_out, const char** names_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WAP_H */

@@ -1,0 +1,396 @@
+// Memory-bound kernels of the training step (gfx950): split-reduction epilogues, ReLU backward,
+// max-pool forward / backward, softmax cross-entropy, SGD, casts.  These are the "auxiliary
+// computation nodes" of Section 3.2.2 and the weight update of Section 3.2.3; all are streaming
+// kernels with 16-byte accesses where the shape allows and a grid sized to cover the chip.
+#include "wap_internal.h"
+
+namespace wap {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+inline int grid_for(size_t work_items) {
+    size_t b = (work_items + kThreads - 1) / kThreads;
+    size_t cap = (size_t)kNumCU * 16;
+    if (b > cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+__device__ __forceinline__ float bf2f(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
+__device__ __forceinline__ unsigned short f2bf(float f) {
+    __bf16 b = (__bf16)f;  // round to nearest even
+    return __builtin_bit_cast(unsigned short, b);
+}
+
+// ---- out[i] = bf16(act(bias[i % ncols] + sum_s part[s][i])) , summed in split order ----
+__global__ void reduce_bf16_kernel(const float* __restrict__ part, int nsplit, size_t elems, int ncols,
+                                   const float* __restrict__ bias, int relu, bf16_t* __restrict__ out) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    if ((ncols & 3) == 0) {
+        size_t n4 = elems / 4;
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+            float4 s = reinterpret_cast<const float4*>(part)[i];
+            for (int k = 1; k < nsplit; ++k) {
+                float4 t = reinterpret_cast<const float4*>(part + (size_t)k * elems)[i];
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            }
+            if (bias) {
+                int c = (int)((i * 4) % (size_t)ncols);
+                s.x += bias[c]; s.y += bias[c + 1]; s.z += bias[c + 2]; s.w += bias[c + 3];
+            }
+            if (relu) {
+                s.x = s.x > 0.f ? s.x : 0.f; s.y = s.y > 0.f ? s.y : 0.f;
+                s.z = s.z > 0.f ? s.z : 0.f; s.w = s.w > 0.f ? s.w : 0.f;
+            }
+            uint2 pk;
+            pk.x = (unsigned)f2bf(s.x) | ((unsigned)f2bf(s.y) << 16);
+            pk.y = (unsigned)f2bf(s.z) | ((unsigned)f2bf(s.w) << 16);
+            reinterpret_cast<uint2*>(out)[i] = pk;
+        }
+    } else {
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < elems; i += stride) {
+            float s = part[i];
+            for (int k = 1; k < nsplit; ++k) s += part[(size_t)k * elems + i];
+            if (bias) s += bias[i % (size_t)ncols];
+            if (relu) s = s > 0.f ? s : 0.f;
+            out[i] = f2bf(s);
+        }
+    }
+}
+
+__global__ void reduce_f32_kernel(const float* __restrict__ part, int nsplit, size_t elems,
+                                  float* __restrict__ out) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    if ((elems & 3) == 0) {
+        size_t n4 = elems / 4;
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+            float4 s = reinterpret_cast<const float4*>(part)[i];
+            for (int k = 1; k < nsplit; ++k) {
+                float4 t = reinterpret_cast<const float4*>(part + (size_t)k * elems)[i];
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            }
+            reinterpret_cast<float4*>(out)[i] = s;
+        }
+    } else {
+        for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < elems; i += stride) {
+            float s = part[i];
+            for (int k = 1; k < nsplit; ++k) s += part[(size_t)k * elems + i];
+            out[i] = s;
+        }
+    }
+}
+
+// ---- ReLU backward ----
+__global__ void relu_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ y,
+                                bf16_t* dx, size_t n) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t n8 = n / 8;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += stride) {
+        uint4 g = reinterpret_cast<const uint4*>(dy)[i];
+        uint4 v = reinterpret_cast<const uint4*>(y)[i];
+        unsigned gg[4] = {g.x, g.y, g.z, g.w}, vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            unsigned lo = (bf2f((unsigned short)(vv[k] & 0xffff)) > 0.f) ? (gg[k] & 0xffffu) : 0u;
+            unsigned hi = (bf2f((unsigned short)(vv[k] >> 16)) > 0.f) ? (gg[k] & 0xffff0000u) : 0u;
+            gg[k] = lo | hi;
+        }
+        reinterpret_cast<uint4*>(dx)[i] = make_uint4(gg[0], gg[1], gg[2], gg[3]);
+    }
+    for (size_t i = n8 * 8 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        dx[i] = (bf2f(y[i]) > 0.f) ? dy[i] : (bf16_t)0;
+}
+
+// ---- max-pool forward: VEC channels per thread ----
+template <int VEC>
+__global__ void maxpool_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
+                                   uint8_t* __restrict__ am, int N, int H, int W, int C, int P, int Q,
+                                   int win, int st) {
+    const int CV = C / VEC;
+    size_t total = (size_t)N * P * Q * CV;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        int cv = (int)(i % CV);
+        size_t t = i / CV;
+        int q = (int)(t % Q); t /= Q;
+        int p = (int)(t % P);
+        int n = (int)(t / P);
+        float best[VEC];
+        unsigned short bestbits[VEC];
+        uint8_t bi[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { best[e] = 0.f; bestbits[e] = 0; bi[e] = 255; }
+        for (int r = 0; r < win; ++r)
+            for (int s = 0; s < win; ++s) {
+                const bf16_t* src = x + (((size_t)n * H + p * st + r) * W + q * st + s) * C + (size_t)cv * VEC;
+                unsigned short v[VEC];
+                if (VEC == 8) {
+                    uint4 u = *reinterpret_cast<const uint4*>(src);
+                    v[0] = u.x & 0xffff; v[1] = u.x >> 16; v[2] = u.y & 0xffff; v[3] = u.y >> 16;
+                    v[4] = u.z & 0xffff; v[5] = u.z >> 16; v[6] = u.w & 0xffff; v[7] = u.w >> 16;
+                } else {
+                    v[0] = src[0];
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    float f = bf2f(v[e]);
+                    if (bi[e] == 255 || f > best[e]) { best[e] = f; bestbits[e] = v[e]; bi[e] = (uint8_t)(r * win + s); }
+                }
+            }
+        size_t o = (((size_t)n * P + p) * Q + q) * C + (size_t)cv * VEC;
+        if (VEC == 8) {
+            *reinterpret_cast<uint4*>(y + o) = make_uint4(
+                (unsigned)bestbits[0] | ((unsigned)bestbits[1] << 16), (unsigned)bestbits[2] | ((unsigned)bestbits[3] << 16),
+                (unsigned)bestbits[4] | ((unsigned)bestbits[5] << 16), (unsigned)bestbits[6] | ((unsigned)bestbits[7] << 16));
+            uint2 a;
+            a.x = bi[0] | (bi[1] << 8) | (bi[2] << 16) | ((unsigned)bi[3] << 24);
+            a.y = bi[4] | (bi[5] << 8) | (bi[6] << 16) | ((unsigned)bi[7] << 24);
+            *reinterpret_cast<uint2*>(am + o) = a;
+        } else {
+            y[o] = bestbits[0];
+            am[o] = bi[0];
+        }
+    }
+}
+
+// ---- max-pool backward as a gather over the windows covering each input element ----
+template <int VEC>
+__global__ void maxpool_bwd_kernel(const bf16_t* __restrict__ dy, const uint8_t* __restrict__ am,
+                                   const bf16_t* __restrict__ ry, bf16_t* __restrict__ dx, int N, int H,
+                                   int W, int C, int P, int Q, int win, int st) {
+    const int CV = C / VEC;
+    size_t total = (size_t)N * H * W * CV;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        int cv = (int)(i % CV);
+        size_t t = i / CV;
+        int w = (int)(t % W); t /= W;
+        int h = (int)(t % H);
+        int n = (int)(t / H);
+        float sum[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sum[e] = 0.f;
+        int p_lo = (h - win + 1 + st - 1);
+        p_lo = p_lo > 0 ? p_lo / st : 0;
+        int p_hi = h / st; if (p_hi > P - 1) p_hi = P - 1;
+        int q_lo = (w - win + 1 + st - 1);
+        q_lo = q_lo > 0 ? q_lo / st : 0;
+        int q_hi = w / st; if (q_hi > Q - 1) q_hi = Q - 1;
+        for (int p = p_lo; p <= p_hi; ++p)
+            for (int q = q_lo; q <= q_hi; ++q) {
+                int code = (h - p * st) * win + (w - q * st);
+                size_t o = (((size_t)n * P + p) * Q + q) * C + (size_t)cv * VEC;
+                if (VEC == 8) {
+                    uint2 a = *reinterpret_cast<const uint2*>(am + o);
+                    uint4 g = *reinterpret_cast<const uint4*>(dy + o);
+                    unsigned gg[4] = {g.x, g.y, g.z, g.w};
+                    unsigned yy[4] = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+                    if (ry) {
+                        uint4 v = *reinterpret_cast<const uint4*>(ry + o);
+                        yy[0] = v.x; yy[1] = v.y; yy[2] = v.z; yy[3] = v.w;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        unsigned ai = ((e < 4 ? a.x : a.y) >> ((e & 3) * 8)) & 0xff;
+                        unsigned short gb = (unsigned short)((gg[e >> 1] >> ((e & 1) * 16)) & 0xffff);
+                        unsigned short yb = (unsigned short)((yy[e >> 1] >> ((e & 1) * 16)) & 0xffff);
+                        if ((int)ai == code && bf2f(yb) > 0.f) sum[e] += bf2f(gb);
+                    }
+                } else {
+                    bool pass = ry ? (bf2f(ry[o]) > 0.f) : true;
+                    if ((int)am[o] == code && pass) sum[0] += bf2f(dy[o]);
+                }
+            }
+        size_t o = (((size_t)n * H + h) * W + w) * C + (size_t)cv * VEC;
+        if (VEC == 8) {
+            *reinterpret_cast<uint4*>(dx + o) = make_uint4(
+                (unsigned)f2bf(sum[0]) | ((unsigned)f2bf(sum[1]) << 16), (unsigned)f2bf(sum[2]) | ((unsigned)f2bf(sum[3]) << 16),
+                (unsigned)f2bf(sum[4]) | ((unsigned)f2bf(sum[5]) << 16), (unsigned)f2bf(sum[6]) | ((unsigned)f2bf(sum[7]) << 16));
+        } else {
+            dx[o] = f2bf(sum[0]);
+        }
+    }
+}
+
+// ---- softmax cross-entropy: one work-group per example ----
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__global__ __launch_bounds__(256) void softmax_xent_kernel(const bf16_t* __restrict__ z,
+                                                           const int32_t* __restrict__ labels, int B,
+                                                           int classes, float* __restrict__ row_loss,
+                                                           bf16_t* __restrict__ dz) {
+    __shared__ float red[4];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bf16_t* zb = z + (size_t)b * classes;
+    float m = -3.0e38f;
+    for (int j = tid; j < classes; j += 256) m = fmaxf(m, bf2f(zb[j]));
+    m = wave_max(m);
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float s = 0.f;
+    for (int j = tid; j < classes; j += 256) s += expf(bf2f(zb[j]) - m);
+    s = wave_sum(s);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    s = (red[0] + red[1]) + (red[2] + red[3]);
+    const float inv = 1.f / s, invB = 1.f / (float)B;
+    const int lab = labels[b];
+    for (int j = tid; j < classes; j += 256) {
+        float p = expf(bf2f(zb[j]) - m) * inv;
+        dz[(size_t)b * classes + j] = f2bf((p - (j == lab ? 1.f : 0.f)) * invB);
+    }
+    if (tid == 0) row_loss[b] = -(bf2f(zb[lab]) - m - logf(s));
+}
+
+// fixed-order mean of B row losses (single work-group tree)
+__global__ __launch_bounds__(256) void loss_mean_kernel(const float* __restrict__ row_loss, int B,
+                                                        float* __restrict__ loss) {
+    __shared__ float sh[256];
+    float s = 0.f;
+    for (int j = threadIdx.x; j < B; j += 256) s += row_loss[j];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = sh[0] / (float)B;
+}
+
+// ---- SGD on fp32 master weights, re-deriving the bf16 compute copy ----
+__global__ void sgd_kernel(size_t n, float* __restrict__ w, const float* __restrict__ dw, float lr,
+                           bf16_t* __restrict__ wb) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t n4 = n / 4;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 a = reinterpret_cast<float4*>(w)[i];
+        float4 g = reinterpret_cast<const float4*>(dw)[i];
+        a.x -= lr * g.x; a.y -= lr * g.y; a.z -= lr * g.z; a.w -= lr * g.w;
+        reinterpret_cast<float4*>(w)[i] = a;
+        if (wb) {
+            uint2 pk;
+            pk.x = (unsigned)f2bf(a.x) | ((unsigned)f2bf(a.y) << 16);
+            pk.y = (unsigned)f2bf(a.z) | ((unsigned)f2bf(a.w) << 16);
+            reinterpret_cast<uint2*>(wb)[i] = pk;
+        }
+    }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        float a = w[i] - lr * dw[i];
+        w[i] = a;
+        if (wb) wb[i] = f2bf(a);
+    }
+}
+
+__global__ void cast_kernel(size_t n, const float* __restrict__ src, bf16_t* __restrict__ dst) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t n4 = n / 4;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 a = reinterpret_cast<const float4*>(src)[i];
+        uint2 pk;
+        pk.x = (unsigned)f2bf(a.x) | ((unsigned)f2bf(a.y) << 16);
+        pk.y = (unsigned)f2bf(a.z) | ((unsigned)f2bf(a.w) << 16);
+        reinterpret_cast<uint2*>(dst)[i] = pk;
+    }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        dst[i] = f2bf(src[i]);
+}
+
+// deterministic small values in (-1, 1) for profiling buffers
+__global__ void fill_kernel(bf16_t* p, size_t n, uint32_t seed) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        uint32_t h = (uint32_t)i * 2654435761u + seed;
+        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        float f = ((float)(h & 0xffff) - 32768.f) * (1.f / 32768.f);
+        p[i] = f2bf(f);
+    }
+}
+
+}  // namespace
+
+int launch_reduce_bf16(const float* part, int nsplit, size_t elems, int ncols, const float* bias,
+                       bool relu, bf16_t* out, hipStream_t st) {
+    hipLaunchKernelGGL(reduce_bf16_kernel, dim3(grid_for(elems / 4 + 1)), dim3(kThreads), 0, st, part,
+                       nsplit, elems, ncols, bias, relu ? 1 : 0, out);
+    return check_launch("reduce_bf16");
+}
+
+int launch_reduce_f32(const float* part, int nsplit, size_t elems, float* out, hipStream_t st) {
+    hipLaunchKernelGGL(reduce_f32_kernel, dim3(grid_for(elems / 4 + 1)), dim3(kThreads), 0, st, part,
+                       nsplit, elems, out);
+    return check_launch("reduce_f32");
+}
+
+int launch_fill_bf16(bf16_t* p, size_t n, uint32_t seed, hipStream_t st) {
+    hipLaunchKernelGGL(fill_kernel, dim3(grid_for(n)), dim3(kThreads), 0, st, p, n, seed);
+    return check_launch("fill");
+}
+
+int launch_relu_bwd(const bf16_t* dy, const bf16_t* y, bf16_t* dx, size_t n, hipStream_t st) {
+    hipLaunchKernelGGL(relu_bwd_kernel, dim3(grid_for(n / 8 + 1)), dim3(kThreads), 0, st, dy, y, dx, n);
+    return check_launch("relu_bwd");
+}
+
+int launch_maxpool_fwd(int N, int H, int W, int C, int win, int stp, const bf16_t* x, bf16_t* y,
+                       uint8_t* am, hipStream_t st) {
+    int P = (H - win) / stp + 1, Q = (W - win) / stp + 1;
+    if ((C & 7) == 0) {
+        size_t total = (size_t)N * P * Q * (C / 8);
+        hipLaunchKernelGGL(maxpool_fwd_kernel<8>, dim3(grid_for(total)), dim3(kThreads), 0, st, x, y, am, N,
+                           H, W, C, P, Q, win, stp);
+    } else {
+        size_t total = (size_t)N * P * Q * C;
+        hipLaunchKernelGGL(maxpool_fwd_kernel<1>, dim3(grid_for(total)), dim3(kThreads), 0, st, x, y, am, N,
+                           H, W, C, P, Q, win, stp);
+    }
+    return check_launch("maxpool_fwd");
+}
+
+int launch_maxpool_bwd(int N, int H, int W, int C, int win, int stp, const bf16_t* dy, const uint8_t* am,
+                       const bf16_t* ry, bf16_t* dx, hipStream_t st) {
+    int P = (H - win) / stp + 1, Q = (W - win) / stp + 1;
+    if ((C & 7) == 0) {
+        size_t total = (size_t)N * H * W * (C / 8);
+        hipLaunchKernelGGL(maxpool_bwd_kernel<8>, dim3(grid_for(total)), dim3(kThreads), 0, st, dy, am, ry,
+                           dx, N, H, W, C, P, Q, win, stp);
+    } else {
+        size_t total = (size_t)N * H * W * C;
+        hipLaunchKernelGGL(maxpool_bwd_kernel<1>, dim3(grid_for(total)), dim3(kThreads), 0, st, dy, am, ry,
+                           dx, N, H, W, C, P, Q, win, stp);
+    }
+    return check_launch("maxpool_bwd");
+}
+
+int launch_softmax_xent(int B, int classes, const bf16_t* z, const int32_t* labels, float* loss,
+                        float* row_loss, bf16_t* dz, hipStream_t st) {
+    hipLaunchKernelGGL(softmax_xent_kernel, dim3(B), dim3(256), 0, st, z, labels, B, classes, row_loss, dz);
+    int rc = check_launch("softmax_xent");
+    if (rc != WAP_OK) return rc;
+    hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, st, row_loss, B, loss);
+    return check_launch("loss_mean");
+}
+
+int launch_sgd(size_t n, float* w, const float* dw, float lr, bf16_t* wb, hipStream_t st) {
+    hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(n / 4 + 1)), dim3(kThreads), 0, st, n, w, dw, lr, wb);
+    return check_launch("sgd");
+}
+
+int launch_cast(size_t n, const float* src, bf16_t* dst, hipStream_t st) {
+    hipLaunchKernelGGL(cast_kernel, dim3(grid_for(n / 4 + 1)), dim3(kThreads), 0, st, n, src, dst);
+    return check_launch("cast");
+}
+
+}  // namespace wap

@@ -1,0 +1,435 @@
+// One replica's whole training step as a precomputed host-side launch list: forward, loss,
+// backward, SGD (what each per-GPU partial graph of Section 3.1 executes between two gradient
+// aggregations; its duration is the sum over layers of t_c in Eq. 1).  The plan owns no device
+// memory: every tensor lives at a fixed offset of one caller-provided arena, all launches go to
+// one stream, nothing allocates or synchronises in wap_step_run.
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "wap_internal.h"
+
+using namespace wap;
+
+namespace {
+
+enum OpKind {
+    OP_CONV_FWD, OP_POOL_FWD, OP_FC_FWD, OP_SOFTMAX, OP_RELU_BWD, OP_POOL_BWD,
+    OP_FC_DX, OP_FC_DW, OP_CONV_WGRAD, OP_CONV_DGRAD, OP_SGD
+};
+
+struct Tensor {
+    std::string name;
+    size_t off, bytes;
+};
+
+struct Op {
+    OpKind kind;
+    std::string name;
+    GemmGeom gg;
+    GemmPlan gp;
+    WgradGeom wg;
+    WgradPlan wp;
+    bool b_tr = false, relu = false;
+    size_t t0 = 0, t1 = 0, t2 = 0, t3 = 0, t4 = 0;  // arena offsets, meaning per kind
+    bool has_t2 = false;
+    int N = 0, H = 0, W = 0, C = 0, win = 0, st = 0;  // pooling / softmax shapes
+    size_t n = 0;
+};
+
+struct ConvL {
+    const char* name;
+    int C, K, R, stride, pad, pool_win, pool_st;
+};
+struct FcL {
+    const char* name;
+    int out;
+    bool relu;
+};
+
+const ConvL kAlexConvs[] = {
+    {"conv1", 3, 64, 11, 4, 2, 3, 2}, {"conv2", 64, 192, 5, 1, 2, 3, 2}, {"conv3", 192, 384, 3, 1, 1, 0, 0},
+    {"conv4", 384, 256, 3, 1, 1, 0, 0}, {"conv5", 256, 256, 3, 1, 1, 3, 2},
+};
+const ConvL kVggConvs[] = {
+    {"conv1_1", 3, 64, 3, 1, 1, 0, 0},    {"conv1_2", 64, 64, 3, 1, 1, 2, 2},   {"conv2_1", 64, 128, 3, 1, 1, 0, 0},
+    {"conv2_2", 128, 128, 3, 1, 1, 2, 2}, {"conv3_1", 128, 256, 3, 1, 1, 0, 0}, {"conv3_2", 256, 256, 3, 1, 1, 0, 0},
+    {"conv3_3", 256, 256, 3, 1, 1, 2, 2}, {"conv4_1", 256, 512, 3, 1, 1, 0, 0}, {"conv4_2", 512, 512, 3, 1, 1, 0, 0},
+    {"conv4_3", 512, 512, 3, 1, 1, 2, 2}, {"conv5_1", 512, 512, 3, 1, 1, 0, 0}, {"conv5_2", 512, 512, 3, 1, 1, 0, 0},
+    {"conv5_3", 512, 512, 3, 1, 1, 2, 2},
+};
+const FcL kFcs[] = {{"fc6", 4096, true}, {"fc7", 4096, true}, {"fc8", 1000, false}};
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+struct wap_step_plan {
+    std::vector<Tensor> tensors;
+    std::vector<Op> ops;
+    size_t arena = 0;
+    double flops = 0;
+    float lr = 0.01f;
+    int B = 0, classes = 1000;
+    size_t ws_off = 0, ws_bytes = 0;
+    size_t n_params = 0;
+    size_t w32_off = 0, dw_off = 0, wb_off = 0;
+
+    size_t add(const std::string& name, size_t bytes) {
+        size_t off = arena;
+        tensors.push_back({name, off, bytes});
+        arena = align_up(arena + bytes, 256);
+        return off;
+    }
+    size_t find(const std::string& name) const {
+        for (const Tensor& t : tensors)
+            if (t.name == name) return t.off;
+        return (size_t)-1;
+    }
+};
+
+namespace {
+
+int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_t st) {
+    void* ws = base + p->ws_off;
+    switch (op.kind) {
+        case OP_CONV_FWD:
+        case OP_FC_FWD:
+        case OP_CONV_DGRAD:
+        case OP_FC_DX:
+            return launch_fwd_like(op.gg, op.b_tr, op.gp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
+                                   nullptr, op.relu, (bf16_t*)(base + op.t2), ws, st);
+        case OP_CONV_WGRAD:
+        case OP_FC_DW:
+            return launch_wgrad(op.wg, op.wp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
+                                (float*)(base + op.t2), ws, st);
+        case OP_POOL_FWD:
+            return launch_maxpool_fwd(op.N, op.H, op.W, op.C, op.win, op.st, (const bf16_t*)(base + op.t0),
+                                      (bf16_t*)(base + op.t1), (uint8_t*)(base + op.t2), st);
+        case OP_POOL_BWD:
+            return launch_maxpool_bwd(op.N, op.H, op.W, op.C, op.win, op.st, (const bf16_t*)(base + op.t0),
+                                      (const uint8_t*)(base + op.t1), (const bf16_t*)(base + op.t2),
+                                      (bf16_t*)(base + op.t3), st);
+        case OP_RELU_BWD:
+            return launch_relu_bwd((const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
+                                   (bf16_t*)(base + op.t2), op.n, st);
+        case OP_SOFTMAX:
+            return launch_softmax_xent(op.N, op.C, (const bf16_t*)(base + op.t0), (const int32_t*)(base + op.t1),
+                                       (float*)(base + op.t2), (float*)(base + op.t3), (bf16_t*)(base + op.t4), st);
+        case OP_SGD:
+            return launch_sgd(op.n, (float*)(base + op.t0), (const float*)(base + op.t1), p->lr,
+                              (bf16_t*)(base + op.t2), st);
+    }
+    return set_error(WAP_EINVAL, "internal: unknown op");
+}
+
+}  // namespace
+
+extern "C" {
+
+int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, float lr, uint32_t flags,
+                         wap_step_plan** out) {
+    if (!net || !out) return set_error(WAP_EINVAL, "step plan: NULL argument");
+    if (minibatch < 1 || image < 1) return set_error(WAP_EINVAL, "step plan: minibatch and image must be >= 1");
+    if (flags & ~1u) return set_error(WAP_EINVAL, "step plan: unknown flag bits 0x%x", flags);
+    const ConvL* convs;
+    int nconv;
+    if (!strcmp(net, "alexnet")) { convs = kAlexConvs; nconv = 5; }
+    else if (!strcmp(net, "vgg16")) { convs = kVggConvs; nconv = 13; }
+    else return set_error(WAP_EINVAL, "step plan: unknown net '%s' (alexnet, vgg16)", net);
+    const bool keep = (flags & 1u) != 0;
+    const int B = minibatch;
+
+    // ---- walk the geometry, validating every layer ----
+    std::vector<wap_conv_desc> cds(nconv);
+    std::vector<int> out_hw(nconv), out_ch(nconv);
+    int h = image;
+    for (int i = 0; i < nconv; ++i) {
+        const ConvL& L = convs[i];
+        wap_conv_desc d = {B, h, h, L.C, L.K, L.R, L.R, L.stride, L.stride, L.pad, L.pad, WAP_RELU};
+        int rc = validate_conv(&d);
+        if (rc != WAP_OK) return rc;
+        cds[i] = d;
+        h = (h + 2 * L.pad - L.R) / L.stride + 1;
+        if (L.pool_win) {
+            if (h < L.pool_win) return set_error(WAP_EINVAL, "step plan: image %d too small for %s's pool", image, L.name);
+            h = (h - L.pool_win) / L.pool_st + 1;
+        }
+        out_hw[i] = h;
+        out_ch[i] = L.K;
+    }
+    const int flat = h * h * convs[nconv - 1].K;
+    std::vector<wap_fc_desc> fds(3);
+    int in_f = flat;
+    for (int i = 0; i < 3; ++i) {
+        wap_fc_desc d = {B, in_f, kFcs[i].out, kFcs[i].relu ? WAP_RELU : 0u};
+        int rc = validate_fc(&d);
+        if (rc != WAP_OK) return rc;
+        fds[i] = d;
+        in_f = kFcs[i].out;
+    }
+
+    wap_step_plan* p = new wap_step_plan();
+    p->B = B;
+    p->lr = lr;
+
+    // ---- parameters: three parallel blocks in the same layer order (one SGD launch) ----
+    std::vector<size_t> poff(nconv + 3), pcount(nconv + 3);
+    size_t np = 0;
+    for (int i = 0; i < nconv + 3; ++i) {
+        size_t cnt = i < nconv ? (size_t)convs[i].K * convs[i].R * convs[i].R * convs[i].C
+                               : (size_t)fds[i - nconv].out_features * fds[i - nconv].in_features;
+        poff[i] = np;
+        pcount[i] = cnt;
+        np += align_up(cnt, 64);
+    }
+    p->n_params = np;
+    p->w32_off = p->add("params.w32", np * 4);
+    p->dw_off = p->add("params.dw", np * 4);
+    p->wb_off = p->add("params.w", np * 2);
+    auto lname = [&](int i) { return std::string(i < nconv ? convs[i].name : kFcs[i - nconv].name); };
+    for (int i = 0; i < nconv + 3; ++i) {
+        p->tensors.push_back({lname(i) + ".w32", p->w32_off + poff[i] * 4, pcount[i] * 4});
+        p->tensors.push_back({lname(i) + ".dw", p->dw_off + poff[i] * 4, pcount[i] * 4});
+        p->tensors.push_back({lname(i) + ".w", p->wb_off + poff[i] * 2, pcount[i] * 2});
+    }
+
+    // ---- activations ----
+    size_t t_input = p->add("input", (size_t)B * image * image * 3 * 2);
+    size_t t_labels = p->add("labels", (size_t)B * 4);
+    size_t t_loss = p->add("loss", 16);
+    size_t t_rowloss = p->add("row_loss", (size_t)B * 4);
+    std::vector<size_t> conv_y(nconv), pool_y(nconv, 0), pool_am(nconv, 0), conv_y_elems(nconv), pool_y_elems(nconv, 0);
+    size_t max_g_elems = (size_t)B * 1000;
+    for (int i = 0; i < nconv; ++i) {
+        const wap_conv_desc& d = cds[i];
+        int P = (d.H + 2 * d.pad_h - d.R) / d.stride_h + 1;
+        conv_y_elems[i] = (size_t)B * P * P * d.K;
+        conv_y[i] = p->add(lname(i) + ".y", conv_y_elems[i] * 2);
+        if (conv_y_elems[i] > max_g_elems) max_g_elems = conv_y_elems[i];
+        if (convs[i].pool_win) {
+            pool_y_elems[i] = (size_t)B * out_hw[i] * out_hw[i] * d.K;
+            pool_y[i] = p->add(lname(i) + ".pool.y", pool_y_elems[i] * 2);
+            pool_am[i] = p->add(lname(i) + ".pool.argmax", pool_y_elems[i]);
+        }
+    }
+    std::vector<size_t> fc_y(3);
+    for (int i = 0; i < 3; ++i) {
+        fc_y[i] = p->add(lname(nconv + i) + ".y", (size_t)B * fds[i].out_features * 2);
+        if ((size_t)B * fds[i].in_features > max_g_elems) max_g_elems = (size_t)B * fds[i].in_features;
+    }
+    size_t gbuf[2] = {0, 0};
+    if (!keep) {
+        gbuf[0] = p->add("gradbuf0", max_g_elems * 2);
+        gbuf[1] = p->add("gradbuf1", max_g_elems * 2);
+    }
+    int gsel = 0;
+    auto new_grad = [&](const std::string& name, size_t elems) -> size_t {
+        if (keep) return p->add(name, elems * 2);
+        size_t off = gbuf[gsel];
+        gsel ^= 1;
+        return off;
+    };
+
+    size_t ws_need = 0;
+    auto push_fwd_like = [&](OpKind kind, const std::string& name, const GemmGeom& g, bool b_tr, bool relu, size_t a,
+                             size_t w, size_t o) {
+        Op op;
+        op.kind = kind; op.name = name; op.gg = g; op.b_tr = b_tr; op.relu = relu;
+        op.gp = plan_fwd_like(g, b_tr);
+        op.t0 = a; op.t1 = w; op.t2 = o;
+        if (op.gp.ws_bytes > ws_need) ws_need = op.gp.ws_bytes;
+        p->ops.push_back(op);
+    };
+    auto push_wgrad = [&](OpKind kind, const std::string& name, const WgradGeom& g, size_t x, size_t dy, size_t dw) {
+        Op op;
+        op.kind = kind; op.name = name; op.wg = g;
+        op.wp = plan_wgrad(g);
+        op.t0 = x; op.t1 = dy; op.t2 = dw;
+        if (op.wp.ws_bytes > ws_need) ws_need = op.wp.ws_bytes;
+        p->ops.push_back(op);
+    };
+
+    // ---- forward ----
+    double flops = 0;
+    size_t cur = t_input;
+    for (int i = 0; i < nconv; ++i) {
+        const wap_conv_desc& d = cds[i];
+        GemmGeom g = geom_conv_fwd(d);
+        push_fwd_like(OP_CONV_FWD, lname(i) + ".fwd", g, false, true, cur, p->wb_off + poff[i] * 2, conv_y[i]);
+        double f = 2.0 * g.M * (double)g.Ncols * g.Kred;
+        flops += (i == 0 ? 2.0 : 3.0) * f;
+        cur = conv_y[i];
+        if (convs[i].pool_win) {
+            Op op;
+            op.kind = OP_POOL_FWD; op.name = lname(i) + ".pool.fwd";
+            op.N = B; op.H = g.OH; op.W = g.OW; op.C = d.K; op.win = convs[i].pool_win; op.st = convs[i].pool_st;
+            op.t0 = cur; op.t1 = pool_y[i]; op.t2 = pool_am[i];
+            p->ops.push_back(op);
+            cur = pool_y[i];
+        }
+    }
+    std::vector<size_t> fc_in(3);
+    for (int i = 0; i < 3; ++i) {
+        fc_in[i] = cur;
+        GemmGeom g = geom_fc_fwd(fds[i]);
+        push_fwd_like(OP_FC_FWD, lname(nconv + i) + ".fwd", g, false, kFcs[i].relu, cur, p->wb_off + poff[nconv + i] * 2,
+                      fc_y[i]);
+        flops += 3.0 * 2.0 * B * (double)fds[i].in_features * fds[i].out_features;
+        cur = fc_y[i];
+    }
+    p->flops = flops;
+
+    // ---- loss ----
+    size_t g_cur = new_grad("g.fc8.y", (size_t)B * 1000);
+    {
+        Op op;
+        op.kind = OP_SOFTMAX; op.name = "softmax_xent";
+        op.N = B; op.C = 1000;
+        op.t0 = fc_y[2]; op.t1 = t_labels; op.t2 = t_loss; op.t3 = t_rowloss; op.t4 = g_cur;
+        p->ops.push_back(op);
+    }
+
+    // ---- backward: FC head ----
+    for (int i = 2; i >= 0; --i) {
+        std::string nm = lname(nconv + i);
+        size_t elems = (size_t)B * fds[i].out_features;
+        if (kFcs[i].relu) {
+            Op op;
+            op.kind = OP_RELU_BWD; op.name = nm + ".relu_bwd";
+            op.n = elems;
+            op.t0 = g_cur; op.t1 = fc_y[i];
+            op.t2 = keep ? p->add("gm." + nm + ".y", elems * 2) : g_cur;
+            p->ops.push_back(op);
+            g_cur = op.t2;
+        }
+        push_wgrad(OP_FC_DW, nm + ".dW", geom_fc_dw(fds[i]), fc_in[i], g_cur, p->dw_off + poff[nconv + i] * 4);
+        if (!keep) gsel = (g_cur == gbuf[0]) ? 1 : 0;
+        std::string in_name = i > 0 ? "g." + lname(nconv + i - 1) + ".y"
+                                    : "g." + lname(nconv - 1) + (convs[nconv - 1].pool_win ? ".pool.y" : ".y");
+        size_t g_in = new_grad(in_name, (size_t)B * fds[i].in_features);
+        push_fwd_like(OP_FC_DX, nm + ".dx", geom_fc_dx(fds[i]), true, false, g_cur, p->wb_off + poff[nconv + i] * 2, g_in);
+        g_cur = g_in;
+    }
+
+    // ---- backward: conv stack ----
+    for (int i = nconv - 1; i >= 0; --i) {
+        std::string nm = lname(i);
+        const wap_conv_desc& d = cds[i];
+        GemmGeom gf = geom_conv_fwd(d);
+        if (!keep) gsel = (g_cur == gbuf[0]) ? 1 : 0;
+        if (convs[i].pool_win) {
+            Op op;
+            op.kind = OP_POOL_BWD; op.name = nm + ".pool_relu_bwd";
+            op.N = B; op.H = gf.OH; op.W = gf.OW; op.C = d.K; op.win = convs[i].pool_win; op.st = convs[i].pool_st;
+            op.t0 = g_cur; op.t1 = pool_am[i]; op.t2 = pool_y[i];
+            op.t3 = new_grad("gm." + nm + ".y", conv_y_elems[i]);
+            p->ops.push_back(op);
+            g_cur = op.t3;
+        } else {
+            Op op;
+            op.kind = OP_RELU_BWD; op.name = nm + ".relu_bwd";
+            op.n = conv_y_elems[i];
+            op.t0 = g_cur; op.t1 = conv_y[i];
+            op.t2 = keep ? p->add("gm." + nm + ".y", conv_y_elems[i] * 2) : g_cur;
+            p->ops.push_back(op);
+            g_cur = op.t2;
+        }
+        size_t x_in = i == 0 ? t_input : (convs[i - 1].pool_win ? pool_y[i - 1] : conv_y[i - 1]);
+        push_wgrad(OP_CONV_WGRAD, nm + ".wgrad", geom_conv_wgrad(d), x_in, g_cur, p->dw_off + poff[i] * 4);
+        if (i > 0) {  // the gradient w.r.t. the input image is not needed
+            if (!keep) gsel = (g_cur == gbuf[0]) ? 1 : 0;
+            std::string in_name = "g." + lname(i - 1) + (convs[i - 1].pool_win ? ".pool.y" : ".y");
+            size_t g_in = new_grad(in_name, (size_t)B * d.H * d.W * d.C);
+            push_fwd_like(OP_CONV_DGRAD, nm + ".dgrad", geom_conv_dgrad(d), true, false, g_cur, p->wb_off + poff[i] * 2,
+                          g_in);
+            g_cur = g_in;
+        }
+    }
+
+    // ---- update ----
+    {
+        Op op;
+        op.kind = OP_SGD; op.name = "sgd";
+        op.n = np;
+        op.t0 = p->w32_off; op.t1 = p->dw_off; op.t2 = p->wb_off;
+        p->ops.push_back(op);
+    }
+    p->ws_bytes = ws_need;
+    p->ws_off = p->add("workspace", ws_need ? ws_need : 256);
+    *out = p;
+    return WAP_OK;
+}
+
+void wap_step_plan_destroy(wap_step_plan* p) { delete p; }
+
+int wap_step_arena_bytes(const wap_step_plan* p, size_t* bytes_out) {
+    if (!p || !bytes_out) return set_error(WAP_EINVAL, "step: NULL argument");
+    *bytes_out = p->arena;
+    return WAP_OK;
+}
+
+int wap_step_num_tensors(const wap_step_plan* p) { return p ? (int)p->tensors.size() : 0; }
+
+int wap_step_tensor(const wap_step_plan* p, int32_t index, const char** name, size_t* offset, size_t* bytes) {
+    if (!p || !name || !offset || !bytes) return set_error(WAP_EINVAL, "step: NULL argument");
+    if (index < 0 || index >= (int)p->tensors.size()) return set_error(WAP_EINVAL, "step: tensor index %d out of range", index);
+    *name = p->tensors[index].name.c_str();
+    *offset = p->tensors[index].off;
+    *bytes = p->tensors[index].bytes;
+    return WAP_OK;
+}
+
+double wap_step_flops(const wap_step_plan* p) { return p ? p->flops : 0.0; }
+int wap_step_num_ops(const wap_step_plan* p) { return p ? (int)p->ops.size() : 0; }
+
+static int check_arena(const wap_step_plan* p, void* arena, size_t arena_bytes) {
+    if (!p || !arena) return set_error(WAP_EINVAL, "step: NULL argument");
+    if ((reinterpret_cast<uintptr_t>(arena) & 255u) != 0) return set_error(WAP_EINVAL, "step: arena is not 256-byte aligned");
+    if (arena_bytes < p->arena) return set_error(WAP_EWORKSPACE, "step: arena has %zu bytes, %zu needed", arena_bytes, p->arena);
+    return WAP_OK;
+}
+
+int wap_step_run(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream) {
+    int rc = check_arena(p, arena, arena_bytes);
+    if (rc != WAP_OK) return rc;
+    unsigned char* base = (unsigned char*)arena;
+    for (const Op& op : p->ops) {
+        rc = run_op(p, op, base, (hipStream_t)stream);
+        if (rc != WAP_OK) return rc;
+    }
+    return WAP_OK;
+}
+
+int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, float* us_out,
+                  const char** names_out) {
+    int rc = check_arena(p, arena, arena_bytes);
+    if (rc != WAP_OK) return rc;
+    if (!us_out || !names_out) return set_error(WAP_EINVAL, "step: NULL argument");
+    unsigned char* base = (unsigned char*)arena;
+    hipStream_t st = (hipStream_t)stream;
+    size_t n = p->ops.size();
+    std::vector<hipEvent_t> ev(2 * n);
+    for (auto& e : ev)
+        if (hipEventCreate(&e) != hipSuccess) return set_error(WAP_EHIP, "hipEventCreate failed");
+    rc = WAP_OK;
+    for (size_t i = 0; i < n && rc == WAP_OK; ++i) {
+        (void)hipEventRecord(ev[2 * i], st);
+        rc = run_op(p, p->ops[i], base, st);
+        (void)hipEventRecord(ev[2 * i + 1], st);
+    }
+    hipError_t e = hipStreamSynchronize(st);
+    if (rc == WAP_OK && e != hipSuccess) rc = set_error(WAP_EHIP, "step: %s", hipGetErrorString(e));
+    if (rc == WAP_OK) {
+        for (size_t i = 0; i < n; ++i) {
+            float ms = 0.f;
+            (void)hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]);
+            us_out[i] = ms * 1000.f;
+            names_out[i] = p->ops[i].name.c_str();
+        }
+    }
+    for (auto& ev_i : ev) (void)hipEventDestroy(ev_i);
+    return rc;
+}
+
+}  // extern "C"

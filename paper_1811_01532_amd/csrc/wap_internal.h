@@ -1,0 +1,103 @@
+// Internal declarations shared by the HIP translation units of libwap (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/wap.h"
+
+namespace wap {
+
+typedef unsigned short bf16_t;  // raw bfloat16 bits in memory
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr double kPeakBf16Tflops = 2516.6;  // 256 CU x 4096 FLOP/clk x 2.4 GHz
+constexpr double kPeakHbmGBs = 8000.0;
+constexpr int kNumCU = 256;
+constexpr int kNumXCD = 8;
+
+// ---- test hook: force a tile configuration / split count (-1 = choose from the shape) ----
+extern int g_force_fwd_cfg, g_force_wgrad_cfg, g_force_nsplit;
+
+// ---- error reporting (thread local) ----
+int set_error(int code, const char* fmt, ...);
+int check_launch(const char* what);
+
+// ---- implicit-GEMM problem, in the form the kernels consume ----
+// Rows m = (n, oh, ow) of the "row space"; reduction index kk = (r, s, ic) with ic innermost;
+// the gathered element is A[n][ih][iw][ic] with th = oh*mul_h - pad_h + r, ih = th/div_h
+// (valid when th >= 0, th % div_h == 0, ih < IH), likewise for the width.
+struct GemmGeom {
+    int IH, IW, IC;
+    int OH, OW;
+    int R, S;
+    int mul_h, mul_w, div_h, div_w, pad_h, pad_w;
+    int M;      // N * OH * OW
+    int Ncols;  // output channels of this product
+    int Kred;   // R * S * IC
+};
+
+// How a forward-type product (rows = pixels, reduction = filter taps x channels) is tiled.
+struct GemmPlan {
+    int cfg;     // tile configuration id
+    int nsplit;  // reduction splits (1 = direct epilogue)
+    size_t ws_bytes;
+};
+
+// Weight operand addressing.
+//  NT : Bw[n][kk]               (forward conv / FC forward): row pitch Kred
+//  TR : Bw[k][R-1-r][S-1-s][n]  (data gradient: reduction (r,s,k), k innermost): n contiguous
+GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr);
+int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
+                    const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
+                    hipStream_t st);
+
+// Weight-gradient product: dw[k][(r,s,c)] = sum over pixels of dy[pix][k] * x[pix @ (r,s)][c].
+struct WgradGeom {
+    int N, H, W, C, K, R, S, sh, sw, ph, pw, P, Q;
+};
+struct WgradPlan {
+    int cfg;
+    int nsplit;
+    size_t ws_bytes;
+};
+WgradPlan plan_wgrad(const WgradGeom& g);
+int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
+                 float* dw, void* ws, hipStream_t st);
+
+// split-reduction epilogues (fixed summation order)
+int launch_reduce_bf16(const float* part, int nsplit, size_t elems, int ncols, const float* bias,
+                       bool relu, bf16_t* out, hipStream_t st);
+int launch_reduce_f32(const float* part, int nsplit, size_t elems, float* out, hipStream_t st);
+
+// fill helpers used by the profiler
+int launch_fill_bf16(bf16_t* p, size_t n, uint32_t seed, hipStream_t st);
+
+// memory-bound kernels
+int launch_relu_bwd(const bf16_t* dy, const bf16_t* y, bf16_t* dx, size_t n, hipStream_t st);
+int launch_maxpool_fwd(int N, int H, int W, int C, int win, int stp, const bf16_t* x, bf16_t* y,
+                       uint8_t* am, hipStream_t st);
+int launch_maxpool_bwd(int N, int H, int W, int C, int win, int stp, const bf16_t* dy, const uint8_t* am,
+                       const bf16_t* ry, bf16_t* dx, hipStream_t st);
+int launch_softmax_xent(int B, int classes, const bf16_t* z, const int32_t* labels, float* loss,
+                        float* row_loss, bf16_t* dz, hipStream_t st);
+int launch_sgd(size_t n, float* w, const float* dw, float lr, bf16_t* wb, hipStream_t st);
+int launch_cast(size_t n, const float* src, bf16_t* dst, hipStream_t st);
+
+// descriptor -> kernel geometry (after validation)
+GemmGeom geom_conv_fwd(const wap_conv_desc& d);
+GemmGeom geom_conv_dgrad(const wap_conv_desc& d);
+WgradGeom geom_conv_wgrad(const wap_conv_desc& d);
+GemmGeom geom_fc_fwd(const wap_fc_desc& d);
+GemmGeom geom_fc_dx(const wap_fc_desc& d);
+WgradGeom geom_fc_dw(const wap_fc_desc& d);
+int validate_conv(const wap_conv_desc* d);
+int validate_fc(const wap_fc_desc* d);
+
+}  // namespace wap
