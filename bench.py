@@ -1,0 +1,299 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-replica training step on one MI355X.
+
+A "step" is one whole pass of the hot path over one synthetic minibatch: forward, softmax
+cross-entropy, backward (data and weight gradients of every conv / FC layer, ReLU and max-pool
+backward) and the SGD update, enqueued from the library's launch list on one stream.
+
+Prints ONE JSON line.  `value` is the step's algorithmic TFLOP/s (direct-convolution FLOP count,
+first layer's data gradient excluded) with all inputs resident in HBM.  `roofline` describes the
+kernel that takes the largest share of the step, timed with HIP events inside the timed region;
+`cpu_baseline` is the fp64 oracle on the host cores over a bounded sample of the same workload;
+`util_table` is the step-level utilisation-versus-per-GPU-minibatch sweep for both networks and
+`layers` the per-layer table of the headline workload (what a workload analysis unit would sum).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+import synth_inputs as si  # noqa: E402
+
+PEAK_BF16 = 2516.6  # TFLOP/s, dense bf16 MFMA
+PEAK_HBM = 8000.0   # GB/s
+
+
+def _arena(plan, torch):
+    buf = torch.empty(plan.arena_bytes() + 256, dtype=torch.uint8, device="cuda")
+    assert buf.data_ptr() % 256 == 0
+    return buf
+
+
+def _view(buf, tensors, name, dtype, torch):
+    off, nb = tensors[name]
+    return buf[off:off + nb].view(dtype)
+
+
+def init_step(plan, buf, net, B, image, torch, wap, recipe):
+    """Fills weights, input and labels.  recipe='numpy' uses the seeded host recipe of
+    synth_inputs (the headline run); 'device' draws the same distributions with torch on the GPU
+    (used for the minibatch sweep, where only timing matters)."""
+    t = plan.tensors()
+    convs, fcs = si.NETS[net]
+    shapes = si.conv_shapes(convs, image)
+    layers = [(d["name"], (d["K"], d["R"], d["S"], d["C"])) for d in shapes]
+    n_in = shapes[-1]["out_hw"] ** 2 * shapes[-1]["K"]
+    for (name, _, n_out, _) in fcs:
+        layers.append((name, (n_out, n_in)))
+        n_in = n_out
+    _view(buf, t, "params.w32", torch.float32, torch).zero_()
+    _view(buf, t, "params.dw", torch.float32, torch).zero_()
+    for i, (name, shape) in enumerate(layers):
+        w32 = _view(buf, t, name + ".w32", torch.float32, torch)
+        fan_in = int(np.prod(shape[1:]))
+        if recipe == "numpy":
+            bits = si.he_weight_bf16(si.rng(5, 10 + i), shape)
+            w = torch.from_numpy(bits.view(np.int16).ravel()).to("cuda").view(torch.bfloat16)
+            w32.copy_(w.to(torch.float32))
+        else:
+            w32.normal_(0.0, float(np.sqrt(2.0 / fan_in)))
+            w32.copy_(w32.to(torch.bfloat16).to(torch.float32))
+    n = t["params.w32"][1] // 4
+    wap.wap_cast_f32_bf16(n, _view(buf, t, "params.w32", torch.float32, torch),
+                          _view(buf, t, "params.w", torch.bfloat16, torch))
+    x = _view(buf, t, "input", torch.bfloat16, torch)
+    lab = _view(buf, t, "labels", torch.int32, torch)
+    if recipe == "numpy":
+        bits = si.normal_bf16(si.rng(5, 0), (B, image, image, 3))
+        x.copy_(torch.from_numpy(bits.view(np.int16).ravel()).to("cuda").view(torch.bfloat16))
+        lab.copy_(torch.from_numpy(si.labels(si.rng(5, 1), B)).to("cuda"))
+    else:
+        x.copy_(torch.randn(x.numel(), device="cuda").to(torch.bfloat16))
+        lab.copy_(torch.randint(0, 1000, (B,), device="cuda", dtype=torch.int32))
+    torch.cuda.synchronize()
+
+
+def time_plain_steps(plan, buf, steps, warmup, torch):
+    for _ in range(warmup):
+        plan.run(buf)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        plan.run(buf)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline(net, image):
+    """The fp64 oracle, as it stands, on one image of the headline network: every conv and FC
+    layer forward + data gradient + weight gradient (first layer's data gradient skipped)."""
+    from oracle import oracle as orc
+    orc.build()
+    convs, fcs = si.NETS[net]
+    shapes = si.conv_shapes(convs, image)
+    g = np.random.default_rng(7)
+    flops = 0.0
+    t0 = time.perf_counter()
+    x = g.standard_normal((1, image, image, 3))
+    for i, d in enumerate(shapes):
+        w = g.standard_normal((d["K"], d["R"], d["S"], d["C"])) * np.sqrt(2.0 / (d["C"] * d["R"] * d["S"]))
+        st, pad = (d["stride"],) * 2, (d["pad"],) * 2
+        y = orc.conv2d_fwd(x, w, st, pad, relu=True)
+        gy = g.standard_normal(y.shape)
+        orc.conv2d_bwd_weight(x, gy, w.shape, st, pad)
+        f = 2.0 * d["P"] * d["Q"] * d["K"] * d["C"] * d["R"] * d["S"]
+        flops += 2 * f
+        if i > 0:
+            orc.conv2d_bwd_data(gy, w, x.shape, st, pad)
+            flops += f
+        x = y
+        if d["pool"]:
+            x, _ = orc.maxpool_fwd(x, d["pool"][0], d["pool"][1])
+    x = x.reshape(1, -1)
+    for (_, _, n_out, relu) in fcs:
+        w = g.standard_normal((n_out, x.shape[1])) * np.sqrt(2.0 / x.shape[1])
+        y = orc.fc_fwd(x, w, relu=relu)
+        gy = g.standard_normal(y.shape)
+        orc.fc_bwd_data(gy, w)
+        orc.fc_bwd_weight(gy, x)
+        flops += 3 * 2.0 * x.shape[1] * n_out
+        x = y
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"{net} one image ({image}x{image}), every conv/FC layer fwd+dgrad+wgrad in fp64, "
+                      f"{flops / 1e9:.1f} GFLOP in {dt:.1f} s (input generation included)"}
+
+
+def load_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--net", default="vgg16", choices=["vgg16", "alexnet"])
+    ap.add_argument("--minibatch", type=int, default=64)
+    ap.add_argument("--no-table", action="store_true", help="skip the minibatch sweep and per-layer table")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--table-out", default=None, help="also write the tables as Markdown to this path")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs one replica on ONE GPU; --gpus above 1 is not supported "
+              "(no collectives, no sharding in this library)", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_1811_01532_amd as wap
+    if not os.path.exists(os.path.join(ROOT, "paper_1811_01532_amd", "libwap.so")):
+        from paper_1811_01532_amd import build
+        build.build(verbose=False)
+    wap.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    net, B, image = a.net, a.minibatch, 224
+
+    plan = wap.StepPlan(net, B, lr=0.01, image=image)
+    buf = _arena(plan, torch)
+    init_step(plan, buf, net, B, image, torch, wap, "numpy")
+    ops = plan.ops()
+    flops_step = plan.flops()
+
+    # warm-up (also creates the cached events), then the timed region: K steps, events around every op
+    plan.time(buf, steps=max(1, a.warmup))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    us = plan.time(buf, steps=a.steps)          # synchronises at its end
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / a.steps * 1e3
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+    loss = float(_view(buf, plan.tensors(), "loss", torch.float32, torch)[0])
+    if not np.isfinite(loss):
+        print(f"bench.py: loss is not finite after the timed steps ({loss})", file=sys.stderr)
+        return 4
+
+    # ---- per-kernel breakdown of the timed region ----
+    kern = {}
+    for (name, kernel, fl, by), u in zip(ops, us):
+        k = kern.setdefault(kernel, {"kernel": kernel, "launches": 0, "us": 0.0, "flops": 0.0, "bytes": 0.0})
+        k["launches"] += 1
+        k["us"] += u
+        k["flops"] += fl
+        k["bytes"] += by
+    klist = sorted(kern.values(), key=lambda k: -k["us"])
+    dom = klist[0]
+    dom_mfma = dom["flops"] > 0
+    if dom_mfma:
+        ach = dom["flops"] / (dom["us"] * 1e-6) / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16, "unit": "TFLOP/s", "frac": ach / PEAK_BF16}
+    else:
+        ach = dom["bytes"] / (dom["us"] * 1e-6) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM, "unit": "GB/s", "frac": ach / PEAK_HBM}
+    roof.update({"traffic": load_traffic(dom["kernel"]), "kernel": dom["kernel"],
+                 "launches_per_step": dom["launches"], "avg_launch_us": dom["us"] / dom["launches"],
+                 "alg_flops_per_launch": dom["flops"] / dom["launches"],
+                 "alg_bytes_per_launch": dom["bytes"] / dom["launches"],
+                 "share_of_step_time": dom["us"] / sum(k["us"] for k in klist)})
+    kernels = [{"kernel": k["kernel"], "launches": k["launches"], "us_per_step": round(k["us"], 2),
+                "tflops": round(k["flops"] / (k["us"] * 1e-6) / 1e12, 2) if k["us"] > 0 else None,
+                "gbs": round(k["bytes"] / (k["us"] * 1e-6) / 1e9, 1) if k["us"] > 0 else None} for k in klist]
+    op_rows = [{"op": name, "kernel": kernel, "us": round(u, 2),
+                "tflops": round(fl / (u * 1e-6) / 1e12, 1) if u > 0 else None,
+                "frac_peak": round(fl / (u * 1e-6) / 1e12 / PEAK_BF16, 4) if u > 0 else None,
+                "gbs": round(by / (u * 1e-6) / 1e9, 1) if u > 0 else None}
+               for (name, kernel, fl, by), u in zip(ops, us)]
+
+    out = {
+        "metric": "step TFLOP/s (bf16 MFMA utilisation) of one replica's training step",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{net} full training step (conv+FC fwd/bwd, ReLU, max-pool, softmax-CE, SGD "
+                               f"lr=0.01), per-GPU minibatch {B}, 3x{image}x{image} input, 1000 classes",
+                   "net": net, "minibatch": B, "step_gflop": flops_step / 1e9, "ops_per_step": len(ops)},
+        "frac_of_bf16_peak": value / PEAK_BF16,
+        "images_per_s": B / (ms_per_step * 1e-3),
+        "loss_after": loss,
+        "roofline": roof,
+        "kernels": kernels,
+        "ops": op_rows,
+    }
+    del buf, plan
+    torch.cuda.empty_cache()
+
+    md = []
+    if not a.no_table:
+        # ---- step-level utilisation versus per-GPU minibatch, both networks ----
+        table = []
+        for tnet in ("alexnet", "vgg16"):
+            for b in (8, 16, 32, 64, 128, 256):
+                p = wap.StepPlan(tnet, b, lr=0.01, image=image)
+                bb = _arena(p, torch)
+                init_step(p, bb, tnet, b, image, torch, wap, "device")
+                sec = time_plain_steps(p, bb, steps=5, warmup=2, torch=torch)
+                tf = p.flops() / sec / 1e12
+                table.append({"net": tnet, "minibatch": b, "ms_per_step": round(sec * 1e3, 4),
+                              "tflops": round(tf, 2), "frac_of_bf16_peak": round(tf / PEAK_BF16, 4),
+                              "images_per_s": round(b / sec, 1), "ops": p.num_ops()})
+                del bb, p
+                torch.cuda.empty_cache()
+        out["util_table"] = table
+        # ---- per-layer table (t_c per pass) of the headline network across the minibatch sweep ----
+        layers = []
+        convs, fcs = si.NETS[net]
+        mbs = [8, 16, 32, 64, 128, 256]
+        descs = [(d["name"], 0, wap.conv_desc(1, d["H"], d["W"], d["C"], d["K"], d["R"], d["S"], d["stride"],
+                                              d["pad"], relu=True)) for d in si.conv_shapes(convs, image)]
+        descs += [(name, 1, wap.fc_desc(1, n_in, n_out, relu)) for (name, n_in, n_out, relu) in fcs]
+        for (name, kind, desc) in descs:
+            nbytes = wap.wap_profile_scratch_bytes(kind, desc, mbs)
+            scratch = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+            rows = wap.wap_profile_layer(kind, desc, mbs, 2, 7, scratch)
+            for r in rows:
+                layers.append({"layer": name, "pass": ("fwd", "dgrad", "wgrad")[r.pass_], "minibatch": r.minibatch,
+                               "us": round(r.time_us_median, 2), "tflops": round(r.tflops, 2),
+                               "frac_peak": round(r.frac_of_bf16_peak, 4), "gbs": round(r.gbytes_per_s, 1),
+                               "bound": ("mfma", "hbm")[r.bound]})
+            del scratch
+            torch.cuda.empty_cache()
+        out["layers"] = layers
+        md.append("| net | minibatch | ms/step | TFLOP/s | frac of bf16 peak | images/s |\n|---|---|---|---|---|---|")
+        for r in table:
+            md.append(f"| {r['net']} | {r['minibatch']} | {r['ms_per_step']} | {r['tflops']} | "
+                      f"{r['frac_of_bf16_peak']} | {r['images_per_s']} |")
+        md.append("\n| layer | pass | minibatch | us | TFLOP/s | frac of peak | GB/s | side of ridge |\n|---|---|---|---|---|---|---|---|")
+        for r in layers:
+            md.append(f"| {r['layer']} | {r['pass']} | {r['minibatch']} | {r['us']} | {r['tflops']} | "
+                      f"{r['frac_peak']} | {r['gbs']} | {r['bound']} |")
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(net, image)
+    if a.table_out and md:
+        with open(a.table_out, "w") as f:
+            f.write("\n".join(md) + "\n")
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -196,10 +196,16 @@ double wap_step_flops(const wap_step_plan* p);
 /* Number of operations in the launch list (an operation is one kernel, or a kernel plus its
  * split-reduction epilogue). */
 int wap_step_num_ops(const wap_step_plan* p);
-/* Runs the step once with a HIP event pair around every operation; fills us_out[num_ops] and
- * names_out[num_ops] (strings owned by the plan, e.g. "conv3_2.wgrad").  Synchronises. */
-int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream,
-                  float* us_out, const char** names_out);
+/* Operation `index` of the launch list: its name (e.g. "conv3_2.wgrad"), the kernel instantiation
+ * it launches, and its algorithmic FLOPs and bytes (operands read once, outputs written once).
+ * Strings are owned by the plan. */
+int wap_step_op_info(const wap_step_plan* p, int32_t index, const char** name, const char** kernel,
+                     double* flops, double* bytes);
+/* Runs `steps` steps back to back with a HIP event pair around every operation (events are created
+ * on first use and cached in the plan); fills us_out[num_ops] with each operation's mean duration
+ * in microseconds.  Synchronises the stream once, at the end. */
+int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
+                  float* us_out);
 
 #ifdef __cplusplus
 }

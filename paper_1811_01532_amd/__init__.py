@@ -229,16 +229,27 @@ class StepPlan:
     def flops(self):
         return lib().wap_step_flops(self._p)
 
-    def num_launches(self):
+    def num_ops(self):
         return lib().wap_step_num_ops(self._p)
 
     def run(self, arena, stream=None):
         _check(lib().wap_step_run(self._p, _ptr(arena), ctypes.c_size_t(_nbytes(arena)), _stream(stream)))
 
-    def time(self, arena, stream=None):
-        """One step with an event pair around every launch: [(name, microseconds)]."""
-        n = self.num_launches()
+    def ops(self):
+        """[(name, kernel, flops, bytes)] for every operation of the launch list."""
+        out = []
+        for i in range(self.num_ops()):
+            name, kern = ctypes.c_char_p(), ctypes.c_char_p()
+            fl, by = ctypes.c_double(0), ctypes.c_double(0)
+            _check(lib().wap_step_op_info(self._p, i, ctypes.byref(name), ctypes.byref(kern), ctypes.byref(fl),
+                                          ctypes.byref(by)))
+            out.append((name.value.decode(), kern.value.decode(), fl.value, by.value))
+        return out
+
+    def time(self, arena, steps=1, stream=None):
+        """`steps` steps with an event pair around every operation: mean microseconds per operation."""
+        n = self.num_ops()
         us = (ctypes.c_float * n)()
-        names = (ctypes.c_char_p * n)()
-        _check(lib().wap_step_time(self._p, _ptr(arena), ctypes.c_size_t(_nbytes(arena)), _stream(stream), us, names))
-        return [(names[i].decode(), float(us[i])) for i in range(n)]
+        _check(lib().wap_step_time(self._p, _ptr(arena), ctypes.c_size_t(_nbytes(arena)), _stream(stream),
+                                   int(steps), us))
+        return [float(us[i]) for i in range(n)]

@@ -479,3 +479,17 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
 }
 
 }  // namespace wap
+
+namespace wap {
+// Label of the kernel instantiation a plan launches (matches the demangled kernel name).
+const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan) {
+    static const char* names[4][2][3] = {
+        {{"igemm_kernel<256,256,2,4,false,0>", "", ""}, {"igemm_kernel<256,256,2,4,true,0>", "", ""}},
+        {{"igemm_kernel<128,128,2,2,false,0>", "igemm_kernel<128,128,2,2,false,1>", "igemm_kernel<128,128,2,2,false,2>"},
+         {"igemm_kernel<128,128,2,2,true,0>", "igemm_kernel<128,128,2,2,true,1>", "igemm_kernel<128,128,2,2,true,2>"}},
+        {{"igemm_kernel<64,256,1,4,false,0>", "", ""}, {"igemm_kernel<64,256,1,4,true,0>", "", ""}},
+        {{"igemm_kernel<256,64,4,1,false,0>", "", ""}, {"igemm_kernel<256,64,4,1,true,0>", "", ""}},
+    };
+    return names[plan.cfg][b_tr ? 1 : 0][classify_mode(g, b_tr)];
+}
+}  // namespace wap

@@ -32,9 +32,10 @@ struct Op {
     WgradPlan wp;
     bool b_tr = false, relu = false;
     size_t t0 = 0, t1 = 0, t2 = 0, t3 = 0, t4 = 0;  // arena offsets, meaning per kind
-    bool has_t2 = false;
     int N = 0, H = 0, W = 0, C = 0, win = 0, st = 0;  // pooling / softmax shapes
     size_t n = 0;
+    const char* kernel = "";  // kernel instantiation the operation launches
+    double flops = 0, bytes = 0;  // algorithmic work: operands read once, outputs written once
 };
 
 struct ConvL {
@@ -74,6 +75,7 @@ struct wap_step_plan {
     size_t ws_off = 0, ws_bytes = 0;
     size_t n_params = 0;
     size_t w32_off = 0, dw_off = 0, wb_off = 0;
+    mutable std::vector<hipEvent_t> events;  // cached by wap_step_time
 
     size_t add(const std::string& name, size_t bytes) {
         size_t off = arena;
@@ -237,6 +239,9 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         Op op;
         op.kind = kind; op.name = name; op.gg = g; op.b_tr = b_tr; op.relu = relu;
         op.gp = plan_fwd_like(g, b_tr);
+        op.kernel = fwd_like_kernel_name(g, b_tr, op.gp);
+        op.flops = 2.0 * g.M * (double)g.Ncols * g.Kred;
+        op.bytes = 2.0 * ((double)B * g.IH * g.IW * g.IC + (double)g.Kred * g.Ncols + (double)g.M * g.Ncols);
         op.t0 = a; op.t1 = w; op.t2 = o;
         if (op.gp.ws_bytes > ws_need) ws_need = op.gp.ws_bytes;
         p->ops.push_back(op);
@@ -245,6 +250,9 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         Op op;
         op.kind = kind; op.name = name; op.wg = g;
         op.wp = plan_wgrad(g);
+        op.kernel = wgrad_kernel_name(g, op.wp);
+        op.flops = 2.0 * g.N * g.P * g.Q * (double)g.K * g.R * g.S * g.C;
+        op.bytes = 2.0 * ((double)g.N * g.H * g.W * g.C + (double)g.N * g.P * g.Q * g.K) + 4.0 * g.K * g.R * g.S * g.C;
         op.t0 = x; op.t1 = dy; op.t2 = dw;
         if (op.wp.ws_bytes > ws_need) ws_need = op.wp.ws_bytes;
         p->ops.push_back(op);
@@ -265,6 +273,8 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             op.kind = OP_POOL_FWD; op.name = lname(i) + ".pool.fwd";
             op.N = B; op.H = g.OH; op.W = g.OW; op.C = d.K; op.win = convs[i].pool_win; op.st = convs[i].pool_st;
             op.t0 = cur; op.t1 = pool_y[i]; op.t2 = pool_am[i];
+            op.kernel = "maxpool_fwd_kernel";
+            op.bytes = 2.0 * conv_y_elems[i] + 3.0 * pool_y_elems[i];
             p->ops.push_back(op);
             cur = pool_y[i];
         }
@@ -287,6 +297,8 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         op.kind = OP_SOFTMAX; op.name = "softmax_xent";
         op.N = B; op.C = 1000;
         op.t0 = fc_y[2]; op.t1 = t_labels; op.t2 = t_loss; op.t3 = t_rowloss; op.t4 = g_cur;
+        op.kernel = "softmax_xent_kernel";
+        op.bytes = 4.0 * B * 1000;
         p->ops.push_back(op);
     }
 
@@ -300,6 +312,8 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             op.n = elems;
             op.t0 = g_cur; op.t1 = fc_y[i];
             op.t2 = keep ? p->add("gm." + nm + ".y", elems * 2) : g_cur;
+            op.kernel = "relu_bwd_kernel";
+            op.bytes = 6.0 * elems;
             p->ops.push_back(op);
             g_cur = op.t2;
         }
@@ -324,6 +338,8 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             op.N = B; op.H = gf.OH; op.W = gf.OW; op.C = d.K; op.win = convs[i].pool_win; op.st = convs[i].pool_st;
             op.t0 = g_cur; op.t1 = pool_am[i]; op.t2 = pool_y[i];
             op.t3 = new_grad("gm." + nm + ".y", conv_y_elems[i]);
+            op.kernel = "maxpool_bwd_kernel";
+            op.bytes = 2.0 * conv_y_elems[i] + 5.0 * pool_y_elems[i];
             p->ops.push_back(op);
             g_cur = op.t3;
         } else {
@@ -332,6 +348,8 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             op.n = conv_y_elems[i];
             op.t0 = g_cur; op.t1 = conv_y[i];
             op.t2 = keep ? p->add("gm." + nm + ".y", conv_y_elems[i] * 2) : g_cur;
+            op.kernel = "relu_bwd_kernel";
+            op.bytes = 6.0 * conv_y_elems[i];
             p->ops.push_back(op);
             g_cur = op.t2;
         }
@@ -353,6 +371,8 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         op.kind = OP_SGD; op.name = "sgd";
         op.n = np;
         op.t0 = p->w32_off; op.t1 = p->dw_off; op.t2 = p->wb_off;
+        op.kernel = "sgd_kernel";
+        op.bytes = 14.0 * np;
         p->ops.push_back(op);
     }
     p->ws_bytes = ws_need;
@@ -361,7 +381,11 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
     return WAP_OK;
 }
 
-void wap_step_plan_destroy(wap_step_plan* p) { delete p; }
+void wap_step_plan_destroy(wap_step_plan* p) {
+    if (!p) return;
+    for (hipEvent_t e : p->events) (void)hipEventDestroy(e);
+    delete p;
+}
 
 int wap_step_arena_bytes(const wap_step_plan* p, size_t* bytes_out) {
     if (!p || !bytes_out) return set_error(WAP_EINVAL, "step: NULL argument");
@@ -401,35 +425,53 @@ int wap_step_run(const wap_step_plan* p, void* arena, size_t arena_bytes, void* 
     return WAP_OK;
 }
 
-int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, float* us_out,
-                  const char** names_out) {
+int wap_step_op_info(const wap_step_plan* p, int32_t index, const char** name, const char** kernel,
+                     double* flops, double* bytes) {
+    if (!p || !name || !kernel || !flops || !bytes) return set_error(WAP_EINVAL, "step: NULL argument");
+    if (index < 0 || index >= (int)p->ops.size()) return set_error(WAP_EINVAL, "step: op index %d out of range", index);
+    const Op& op = p->ops[index];
+    *name = op.name.c_str();
+    *kernel = op.kernel;
+    *flops = op.flops;
+    *bytes = op.bytes;
+    return WAP_OK;
+}
+
+int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
+                  float* us_out) {
     int rc = check_arena(p, arena, arena_bytes);
     if (rc != WAP_OK) return rc;
-    if (!us_out || !names_out) return set_error(WAP_EINVAL, "step: NULL argument");
+    if (!us_out || steps < 1) return set_error(WAP_EINVAL, "step: bad argument");
     unsigned char* base = (unsigned char*)arena;
     hipStream_t st = (hipStream_t)stream;
-    size_t n = p->ops.size();
-    std::vector<hipEvent_t> ev(2 * n);
-    for (auto& e : ev)
+    const size_t n = p->ops.size();
+    const size_t need = 2 * n * (size_t)steps;
+    while (p->events.size() < need) {
+        hipEvent_t e;
         if (hipEventCreate(&e) != hipSuccess) return set_error(WAP_EHIP, "hipEventCreate failed");
-    rc = WAP_OK;
-    for (size_t i = 0; i < n && rc == WAP_OK; ++i) {
-        (void)hipEventRecord(ev[2 * i], st);
-        rc = run_op(p, p->ops[i], base, st);
-        (void)hipEventRecord(ev[2 * i + 1], st);
+        p->events.push_back(e);
     }
+    for (int s = 0; s < steps && rc == WAP_OK; ++s)
+        for (size_t i = 0; i < n && rc == WAP_OK; ++i) {
+            hipEvent_t* ev = &p->events[2 * ((size_t)s * n + i)];
+            (void)hipEventRecord(ev[0], st);
+            rc = run_op(p, p->ops[i], base, st);
+            (void)hipEventRecord(ev[1], st);
+        }
     hipError_t e = hipStreamSynchronize(st);
     if (rc == WAP_OK && e != hipSuccess) rc = set_error(WAP_EHIP, "step: %s", hipGetErrorString(e));
-    if (rc == WAP_OK) {
-        for (size_t i = 0; i < n; ++i) {
+    if (rc != WAP_OK) return rc;
+    for (size_t i = 0; i < n; ++i) {
+        double sum = 0;
+        for (int s = 0; s < steps; ++s) {
             float ms = 0.f;
-            (void)hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]);
-            us_out[i] = ms * 1000.f;
-            names_out[i] = p->ops[i].name.c_str();
+            hipEvent_t* ev = &p->events[2 * ((size_t)s * n + i)];
+            (void)hipEventElapsedTime(&ms, ev[0], ev[1]);
+            sum += ms;
         }
+        us_out[i] = (float)(sum * 1000.0 / steps);
     }
-    for (auto& ev_i : ev) (void)hipEventDestroy(ev_i);
-    return rc;
+    return WAP_OK;
 }
 
 }  // extern "C"

@@ -71,6 +71,9 @@ WgradPlan plan_wgrad(const WgradGeom& g);
 int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
                  float* dw, void* ws, hipStream_t st);
 
+const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan);
+const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan);
+
 // split-reduction epilogues (fixed summation order)
 int launch_reduce_bf16(const float* part, int nsplit, size_t elems, int ncols, const float* bias,
                        bool relu, bf16_t* out, hipStream_t st);

@@ -351,3 +351,14 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
 }
 
 }  // namespace wap
+
+namespace wap {
+const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan) {
+    static const char* names[3][2] = {
+        {"wgrad_kernel<256,256,2,4,0>", ""},
+        {"wgrad_kernel<128,128,2,2,0>", "wgrad_kernel<128,128,2,2,1>"},
+        {"wgrad_kernel<256,64,4,1,0>", ""},
+    };
+    return names[plan.cfg][classify_mode(g)];
+}
+}  // namespace wap

@@ -1,0 +1,134 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_1811_01532_amd", "libwap.so")
+
+
+@pytest.fixture(scope="module")
+def wap():
+    import paper_1811_01532_amd as w
+    if not os.path.exists(LIB):
+        from paper_1811_01532_amd import build
+        build.build(verbose=False)
+    w.lib()
+    return w
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "wap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wap_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(wap):
+    names = _declared_symbols()
+    assert "wap_conv2d_fwd" in names and "wap_profile_layer" in names and "wap_step_run" in names
+    lib = ctypes.CDLL(LIB)
+    missing = [n for n in names if not hasattr(lib, n)]
+    assert not missing, missing
+    assert wap.wap_version() >= 100
+
+
+def test_descriptor_struct_sizes_match_the_header(wap):
+    assert ctypes.sizeof(wap.ConvDesc) == 12 * 4
+    assert ctypes.sizeof(wap.FcDesc) == 4 * 4
+    assert ctypes.sizeof(wap.ProfileRow) == 2 * 4 + 8 * 8 + 2 * 4
+
+
+def _expect(wap, status, fn, *args):
+    with pytest.raises(wap.WapError) as ei:
+        fn(*args)
+    assert ei.value.status == status, str(ei.value)
+    assert len(str(ei.value)) > 20
+
+
+def test_conv_descriptor_validation(wap):
+    ok = wap.conv_desc(4, 32, 32, 3, 16, 3, 3, 1, 1)
+    assert wap.wap_conv2d_workspace_bytes(ok, wap.WAP_PASS_FWD) >= 0
+    for bad in (wap.conv_desc(0, 32, 32, 3, 16, 3, 3, 1, 1),
+                wap.conv_desc(4, 32, 32, 3, 16, 3, 3, 0, 1),
+                wap.conv_desc(4, 32, 32, 3, 16, 3, 3, 1, 3),       # pad >= filter
+                wap.conv_desc(4, 32, 32, 3, 16, 3, 3, 1, -1),
+                wap.conv_desc(1, 2, 2, 3, 16, 7, 7, 1, 1)):        # filter larger than padded input
+        _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_workspace_bytes, bad, wap.WAP_PASS_FWD)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_workspace_bytes, ok, 7)
+    big = wap.conv_desc(4096, 1024, 1024, 64, 64, 3, 3, 1, 1)
+    _expect(wap, wap.WAP_EUNSUPPORTED, wap.wap_conv2d_workspace_bytes, big, wap.WAP_PASS_FWD)
+    flags = wap.conv_desc(4, 32, 32, 3, 16, 3, 3, 1, 1)
+    flags.flags = 0x80
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_workspace_bytes, flags, wap.WAP_PASS_FWD)
+
+
+def test_null_and_misaligned_pointers_are_rejected_before_any_launch(wap):
+    d = wap.conv_desc(4, 32, 32, 64, 64, 3, 3, 1, 1)
+    s = 0  # null stream; never reached
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_fwd, d, None, 4096, None, 8192, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_fwd, d, 4096, 4096 + 2, None, 8192, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_data, d, 4096, 4096, None, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_weight, d, 4096, None, 4096, None, s)
+    f = wap.fc_desc(32, 256, 1000)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_fc_fwd, f, 4096, None, None, 4096, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_fc_bwd, f, 4096, 4096, 4096, None, None, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_relu_bwd, 4096, 4096, None, 10, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_relu_bwd, 4096, 4096, 4096, 0, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_maxpool_fwd, 1, 2, 2, 8, 3, 2, 4096, 4096, 4096, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_softmax_xent_grad, 0, 1000, 4096, 4096, 4096, 4096, 4096, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_sgd_update, 16, None, 4096, 0.01, None, s)
+
+
+def test_workspace_too_small_is_reported(wap):
+    # a shape whose weight gradient needs a split reduction
+    d = wap.conv_desc(8, 28, 28, 256, 256, 3, 3, 1, 1)
+    need = wap.wap_conv2d_workspace_bytes(d, wap.WAP_PASS_BWD_WEIGHT)
+    assert need > 0
+    with pytest.raises(wap.WapError) as ei:
+        wap.lib().wap_conv2d_bwd_weight  # symbol exists
+        wap._check(wap.lib().wap_conv2d_bwd_weight(ctypes.byref(d), ctypes.c_void_p(4096), ctypes.c_void_p(4096),
+                                                   ctypes.c_void_p(4096), ctypes.c_void_p(4096),
+                                                   ctypes.c_size_t(need - 1), ctypes.c_void_p(0)))
+    assert ei.value.status == wap.WAP_EWORKSPACE
+    with pytest.raises(wap.WapError) as ei:
+        wap._check(wap.lib().wap_conv2d_bwd_weight(ctypes.byref(d), ctypes.c_void_p(4096), ctypes.c_void_p(4096),
+                                                   ctypes.c_void_p(4096), ctypes.c_void_p(0), ctypes.c_size_t(0),
+                                                   ctypes.c_void_p(0)))
+    assert ei.value.status == wap.WAP_EWORKSPACE
+
+
+def test_step_plan_is_host_only_and_counts_flops(wap):
+    import synth_inputs as si
+    for net in ("alexnet", "vgg16"):
+        p = wap.StepPlan(net, 32)
+        assert abs(p.flops() / 32 - si.step_flops_per_image(net)) < 1e-6 * si.step_flops_per_image(net)
+        t = p.tensors()
+        assert "input" in t and "labels" in t and "loss" in t and "params.w32" in t and "workspace" in t
+        total = p.arena_bytes()
+        assert all(off + nb <= total for (off, nb) in t.values())
+        assert p.num_ops() > 30
+    with pytest.raises(wap.WapError):
+        wap.StepPlan("resnet", 32)
+    with pytest.raises(wap.WapError):
+        wap.StepPlan("alexnet", 0)
+    with pytest.raises(wap.WapError):
+        wap.StepPlan("alexnet", 2, image=16)   # too small for the pooling chain
+    # tensors of a plan never overlap unless they are views of the parameter blocks or ping-pong buffers
+    p = wap.StepPlan("vgg16", 2, image=32, flags=wap.WAP_STEP_KEEP_GRADS)
+    t = p.tensors()
+    plain = sorted((off, nb, n) for n, (off, nb) in t.items()
+                   if not (n.endswith(".w32") or n.endswith(".dw") or n.endswith(".w")) or n.startswith("params."))
+    for (o1, n1, a), (o2, _, b) in zip(plain, plain[1:]):
+        assert o1 + n1 <= o2, (a, b)
+
+
+def test_profile_argument_checks(wap):
+    d = wap.conv_desc(1, 14, 14, 64, 64, 3, 3, 1, 1)
+    assert wap.wap_profile_scratch_bytes(0, d, [8, 16]) > 0
+    with pytest.raises(wap.WapError):
+        wap.wap_profile_scratch_bytes(2, d, [8])
+    with pytest.raises(wap.WapError):
+        wap.wap_profile_layer(0, d, [8], 1, 1, None, 0)

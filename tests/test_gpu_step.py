@@ -1,0 +1,196 @@
+"""GPU parity of the whole training step (forward, loss, backward, SGD) run from the launch list.
+
+Teacher-forced: every operation's output is compared with the oracle applied to that operation's
+actual device inputs, so rounding differences do not compound across layers.  Reduced image sizes
+keep the fp64 oracle fast; the layer lists are the full AlexNet-style and VGG-16 ones.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+LR = 0.01
+
+
+class Arena:
+    def __init__(self, plan):
+        self.plan = plan
+        self.t = plan.tensors()
+        self.buf = torch.zeros(plan.arena_bytes() + 256, dtype=torch.uint8, device="cuda")
+        assert self.buf.data_ptr() % 256 == 0
+
+    def raw(self, name):
+        off, nb = self.t[name]
+        return self.buf[off:off + nb]
+
+    def bf16(self, name, shape):
+        return self.raw(name).view(torch.bfloat16).view(*shape)
+
+    def f32(self, name, shape):
+        return self.raw(name).view(torch.float32).view(*shape)
+
+    def put_bf16(self, name, bits):
+        self.raw(name).view(torch.int16).copy_(torch.from_numpy(bits.view(np.int16).ravel()))
+
+    def put_f32(self, name, arr):
+        self.raw(name).view(torch.float32).copy_(torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32).ravel()))
+
+
+def _setup(net, B, image, flags, seed_cfg):
+    import paper_1811_01532_amd as wap
+    plan = wap.StepPlan(net, B, lr=LR, image=image, flags=flags)
+    ar = Arena(plan)
+    convs, fcs = si.NETS[net]
+    shapes = si.conv_shapes(convs, image)
+    weights = {}
+    for i, d in enumerate(shapes):
+        wb = si.he_weight_bf16(si.rng(seed_cfg, 10 + i), (d["K"], d["R"], d["S"], d["C"]))
+        weights[d["name"]] = wb
+    flat = shapes[-1]["out_hw"] ** 2 * shapes[-1]["K"]
+    n_in = flat
+    fc_dims = []
+    for j, (name, _, n_out, relu) in enumerate(fcs):
+        wb = si.he_weight_bf16(si.rng(seed_cfg, 40 + j), (n_out, n_in))
+        weights[name] = wb
+        fc_dims.append((name, n_in, n_out, relu))
+        n_in = n_out
+    from oracle import oracle as orc
+    for name, wb in weights.items():
+        ar.put_f32(name + ".w32", orc.bf16_bits_to_f64(wb).astype(np.float32))
+        ar.put_bf16(name + ".w", wb)
+    xb = si.normal_bf16(si.rng(seed_cfg, 0), (B, image, image, 3))
+    labels = si.labels(si.rng(seed_cfg, 1), B)
+    ar.put_bf16("input", xb)
+    ar.raw("labels").view(torch.int32).copy_(torch.from_numpy(labels))
+    return plan, ar, shapes, fc_dims, weights, xb, labels
+
+
+@pytest.mark.parametrize("net,B,image", [("vgg16", 2, 32), ("alexnet", 3, 67)])
+def test_step_every_operation_matches_oracle(orc, net, B, image):
+    import paper_1811_01532_amd as wap
+    plan, ar, shapes, fc_dims, weights, xb, labels = _setup(net, B, image, wap.WAP_STEP_KEEP_GRADS, 500)
+    print(f"[case] step {net} B={B} image={image} ops={plan.num_ops()}", flush=True)
+    plan.run(ar.buf)
+    torch.cuda.synchronize()
+    f64 = orc.bf16_bits_to_f64
+    w64 = {k: f64(v) for k, v in weights.items()}
+
+    def check_bf16(name, got_t, ref, tol=gu.TOL_BF16_OUT):
+        e = gu.rel_err(gu.host_f64(got_t), ref)
+        assert e <= gu.TOL and e <= tol, f"{net} {name}: rel err {e}"
+
+    # ---------------- forward ----------------
+    cur = f64(xb)
+    acts = {}
+    for d in shapes:
+        L = d["name"]
+        y = ar.bf16(L + ".y", (B, d["P"], d["Q"], d["K"]))
+        ref = orc.conv2d_fwd(cur, w64[L], (d["stride"],) * 2, (d["pad"],) * 2, relu=True)
+        check_bf16(L + ".fwd", y, ref)
+        acts[L + ".in"] = cur
+        cur = gu.host_f64(y)
+        acts[L + ".y"] = cur
+        if d["pool"]:
+            win, st = d["pool"]
+            o = d["out_hw"]
+            py = ar.bf16(L + ".pool.y", (B, o, o, d["K"]))
+            am = ar.raw(L + ".pool.argmax").view(B, o, o, d["K"]).cpu().numpy()
+            yref, amref = orc.maxpool_fwd(cur, win, st)
+            assert np.array_equal(gu.host_f64(py), yref), L + ".pool.fwd"
+            assert np.array_equal(am, amref), L + ".pool.argmax"
+            cur = yref
+            acts[L + ".pool.y"] = cur
+            acts[L + ".pool.am"] = am
+    cur = cur.reshape(B, -1)
+    for (name, n_in, n_out, relu) in fc_dims:
+        y = ar.bf16(name + ".y", (B, n_out))
+        ref = orc.fc_fwd(cur, w64[name], relu=relu)
+        check_bf16(name + ".fwd", y, ref)
+        acts[name + ".in"] = cur
+        cur = gu.host_f64(y)
+        acts[name + ".y"] = cur
+    # ---------------- loss ----------------
+    lref, dzref = orc.softmax_xent(cur, labels)
+    loss = float(ar.f32("loss", (4,))[0])
+    assert abs(loss - lref) <= 1e-5 * max(1.0, abs(lref))
+    g_t = ar.bf16("g.fc8.y", (B, 1000))
+    check_bf16("softmax.dz", g_t, dzref)
+    # ---------------- backward: FC ----------------
+    g = gu.host_f64(g_t)
+    last = shapes[-1]
+    last_out = last["name"] + (".pool.y" if last["pool"] else ".y")
+    for idx in range(len(fc_dims) - 1, -1, -1):
+        name, n_in, n_out, relu = fc_dims[idx]
+        if relu:
+            gm_t = ar.bf16("gm." + name + ".y", (B, n_out))
+            ref = orc.relu_bwd(g, acts[name + ".y"])
+            assert np.array_equal(gu.host_f64(gm_t), ref), name + ".relu_bwd"
+            g = ref
+        dW = ar.f32(name + ".dw", (n_out, n_in))
+        e = gu.rel_err(gu.host_f64(dW), orc.fc_bwd_weight(g, acts[name + ".in"]))
+        assert e <= gu.TOL_F32_OUT, f"{name}.dW rel err {e}"
+        in_name = "g." + (fc_dims[idx - 1][0] + ".y" if idx > 0 else last_out)
+        gi_t = ar.bf16(in_name, (B, n_in))
+        check_bf16(name + ".dx", gi_t, orc.fc_bwd_data(g, w64[name]))
+        g = gu.host_f64(gi_t)
+    # ---------------- backward: conv stack ----------------
+    for i in range(len(shapes) - 1, -1, -1):
+        d = shapes[i]
+        L = d["name"]
+        yshape = (B, d["P"], d["Q"], d["K"])
+        gm_t = ar.bf16("gm." + L + ".y", yshape)
+        if d["pool"]:
+            win, st = d["pool"]
+            o = d["out_hw"]
+            routed = orc.maxpool_bwd(g.reshape(B, o, o, d["K"]), acts[L + ".pool.am"], yshape, win, st)
+            ref = orc.relu_bwd(routed, acts[L + ".y"])
+            check_bf16(L + ".pool_relu_bwd", gm_t, ref)
+        else:
+            ref = orc.relu_bwd(g.reshape(yshape), acts[L + ".y"])
+            assert np.array_equal(gu.host_f64(gm_t), ref), L + ".relu_bwd"
+        g = gu.host_f64(gm_t)
+        dw = ar.f32(L + ".dw", (d["K"], d["R"], d["S"], d["C"]))
+        refdw = orc.conv2d_bwd_weight(acts[L + ".in"], g, (d["K"], d["R"], d["S"], d["C"]),
+                                      (d["stride"],) * 2, (d["pad"],) * 2)
+        e = gu.rel_err(gu.host_f64(dw), refdw)
+        assert e <= gu.TOL_F32_OUT, f"{L}.wgrad rel err {e}"
+        if i > 0:
+            prev = shapes[i - 1]
+            in_name = "g." + prev["name"] + (".pool.y" if prev["pool"] else ".y")
+            xshape = (B, d["H"], d["W"], d["C"])
+            gi_t = ar.bf16(in_name, xshape)
+            refdx = orc.conv2d_bwd_data(g, w64[L], xshape, (d["stride"],) * 2, (d["pad"],) * 2)
+            check_bf16(L + ".dgrad", gi_t, refdx)
+            g = gu.host_f64(gi_t)
+    # ---------------- SGD ----------------
+    for name, wb in weights.items():
+        shape = wb.shape
+        dw = gu.host_f64(ar.f32(name + ".dw", shape))
+        w_after = gu.host_f64(ar.f32(name + ".w32", shape))
+        ref = orc.sgd(w64[name], dw, float(np.float32(LR)))
+        assert np.max(np.abs(w_after - ref)) <= 2.0 ** -22 * max(1e-30, np.max(np.abs(ref))), name + ".sgd"
+        wb_after = gu.host_f64(ar.bf16(name + ".w", shape))
+        assert np.array_equal(wb_after, orc.round_bf16(w_after)), name + ".w bf16 copy"
+
+
+def test_step_without_kept_gradients_is_bitwise_the_same(orc):
+    """The ping-pong gradient buffers of the production plan give the same gradients and loss."""
+    import paper_1811_01532_amd as wap
+    res = []
+    for flags in (wap.WAP_STEP_KEEP_GRADS, 0):
+        plan, ar, shapes, fc_dims, weights, _, _ = _setup("vgg16", 2, 32, flags, 501)
+        print(f"[case] step vgg16 flags={flags}", flush=True)
+        plan.run(ar.buf)
+        plan.run(ar.buf)   # a second step on the updated weights
+        torch.cuda.synchronize()
+        n = ar.t["params.dw"][1] // 4
+        res.append((ar.f32("params.dw", (n,)).clone(), ar.f32("params.w32", (n,)).clone(),
+                    ar.f32("loss", (4,))[0].item()))
+    assert torch.equal(res[0][0], res[1][0])
+    assert torch.equal(res[0][1], res[1][1])
+    assert res[0][2] == res[1][2]
+    assert np.isfinite(res[0][2])
