@@ -202,10 +202,11 @@ int wap_step_num_ops(const wap_step_plan* p);
 int wap_step_op_info(const wap_step_plan* p, int32_t index, const char** name, const char** kernel,
                      double* flops, double* bytes);
 /* Runs `steps` steps back to back with a HIP event pair around every operation (events are created
- * on first use and cached in the plan); fills us_out[num_ops] with each operation's mean duration
- * in microseconds.  Synchronises the stream once, at the end. */
+ * on first use and cached in the plan); fills us_out[num_ops] with the mean duration in microseconds
+ * of each operation's main kernel and us_epilogue_out[num_ops] with that of its split-reduction
+ * epilogue kernel (0 where the operation has none).  Synchronises the stream once, at the end. */
 int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
-                  float* us_out);
+                  float* us_out, float* us_epilogue_out);
 
 #ifdef __cplusplus
 }

@@ -206,9 +206,12 @@ class StepPlan:
         self.net, self.minibatch, self.image = net, minibatch, image
 
     def __del__(self):
-        if getattr(self, "_p", None) and self._p.value:
-            lib().wap_step_plan_destroy(self._p)
-            self._p = ctypes.c_void_p(0)
+        try:
+            if getattr(self, "_p", None) and self._p.value:
+                lib().wap_step_plan_destroy(self._p)
+                self._p = ctypes.c_void_p(0)
+        except Exception:  # interpreter shutdown
+            pass
 
     def arena_bytes(self):
         out = ctypes.c_size_t(0)
@@ -247,9 +250,10 @@ class StepPlan:
         return out
 
     def time(self, arena, steps=1, stream=None):
-        """`steps` steps with an event pair around every operation: mean microseconds per operation."""
+        """`steps` steps with events around every operation: (main-kernel us, epilogue-kernel us) lists."""
         n = self.num_ops()
         us = (ctypes.c_float * n)()
+        epi = (ctypes.c_float * n)()
         _check(lib().wap_step_time(self._p, _ptr(arena), ctypes.c_size_t(_nbytes(arena)), _stream(stream),
-                                   int(steps), us))
-        return [float(us[i]) for i in range(n)]
+                                   int(steps), us, epi))
+        return [float(us[i]) for i in range(n)], [float(epi[i]) for i in range(n)]

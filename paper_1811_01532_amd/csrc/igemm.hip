@@ -42,16 +42,22 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
     return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
-__device__ __forceinline__ uint4 ld16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ u32x4 ld16(const bf16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+// Out-of-image taps and tile tails load from this zero block instead of being masked after the load:
+// the loaded registers then have no consumer until the LDS store that follows the MFMAs, so the
+// global-load latency overlaps the current tile's compute.
+__device__ __align__(16) unsigned int g_zero_block[4] = {0u, 0u, 0u, 0u};
 
 __device__ __forceinline__ unsigned short f2bf(float f) {
     __bf16 b = (__bf16)f;  // round to nearest even
     return __builtin_bit_cast(unsigned short, b);
 }
 
-__device__ __forceinline__ uint4 pack8(const unsigned short* h) {
-    return make_uint4((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16),
-                      (unsigned)h[4] | ((unsigned)h[5] << 16), (unsigned)h[6] | ((unsigned)h[7] << 16));
+__device__ __forceinline__ u32x4 pack8(const unsigned short* h) {
+    u32x4 v = {(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16),
+               (unsigned)h[4] | ((unsigned)h[5] << 16), (unsigned)h[6] | ((unsigned)h[7] << 16)};
+    return v;
 }
 
 // MODE 0: fast  -- channel counts multiples of 64 / 8, unit tap divisor, 16-byte loads, one tap per tile
@@ -112,7 +118,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const KAr
     }
     const int b_vec = tid % B_VPR, b_row0 = tid / B_VPR;
 
-    uint4 ra[A_PASSES], rb[B_PASSES];
+    u32x4 ra[A_PASSES], rb[B_PASSES];
+    const bf16_t* zero_src = reinterpret_cast<const bf16_t*>(g_zero_block);
 
     auto tap_ok = [&](int th, int tw, int& ih, int& iw) -> bool {
         if (MODE == 0) {
@@ -128,7 +135,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const KAr
     };
 
     auto load_global = [&](int kt) {
-        const int kk0 = kt * BK;
+        // Fast mode walks the reduction channel-slice-major (all filter taps of one 64-channel slice
+        // before the next slice): the 9 (or 25) shifted re-reads of the same input pixels then happen
+        // in consecutive tiles and hit in L2 instead of going back to HBM.
+        const int RS = g.R * g.S;
+        const int kk0 = (MODE == 0) ? ((kt % RS) * g.IC + (kt / RS) * BK) : kt * BK;
         // ---------- gathered operand ----------
         if (MODE <= 1) {
             int kk = (MODE == 0) ? kk0 : kk0 + a_vec * 8;
@@ -140,10 +151,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const KAr
             for (int i = 0; i < A_PASSES; ++i) {
                 int ih, iw;
                 bool ok = tap_ok(hb[i] + r, wb[i] + s, ih, iw) && kok;
-                int off = ok ? abase[i] + (ih * g.IW + iw) * g.IC + c : 0;
-                uint4 v = ld16(a.A + off);
-                if (!ok) v = make_uint4(0, 0, 0, 0);
-                ra[i] = v;
+                int off = abase[i] + (ih * g.IW + iw) * g.IC + c;
+                ra[i] = ld16(ok ? a.A + off : zero_src);
             }
         } else {
             int rr[8], ss[8], cc[8];
@@ -163,9 +172,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const KAr
                 for (int e = 0; e < 8; ++e) {
                     int ih, iw;
                     bool ok = tap_ok(hb[i] + rr[e], wb[i] + ss[e], ih, iw);
-                    int off = ok ? abase[i] + (ih * g.IW + iw) * g.IC + cc[e] : 0;
-                    unsigned short v = a.A[off];
-                    h16[e] = ok ? v : (unsigned short)0;
+                    int off = abase[i] + (ih * g.IW + iw) * g.IC + cc[e];
+                    h16[e] = *(ok ? a.A + off : zero_src);
                 }
                 ra[i] = pack8(h16);
             }
@@ -179,18 +187,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const KAr
                 int n = n0 + b_row0 + i * B_RPP;
                 if (MODE <= 1) {
                     bool ok = n < g.Ncols && kk < g.Kred;
-                    int off = ok ? n * g.Kred + kk : 0;
-                    uint4 v = ld16(a.Bw + off);
-                    if (!ok) v = make_uint4(0, 0, 0, 0);
-                    rb[i] = v;
+                    rb[i] = ld16(ok ? a.Bw + (n * g.Kred + kk) : zero_src);
                 } else {
                     unsigned short h16[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         bool ok = n < g.Ncols && (kk + e) < g.Kred;
-                        int off = ok ? n * g.Kred + kk + e : 0;
-                        unsigned short v = a.Bw[off];
-                        h16[e] = ok ? v : (unsigned short)0;
+                        h16[e] = *(ok ? a.Bw + (n * g.Kred + kk + e) : zero_src);
                     }
                     rb[i] = pack8(h16);
                 }
@@ -207,18 +210,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const KAr
                 int rowoff = ((k * g.R + (g.R - 1 - r)) * g.S + (g.S - 1 - s)) * g.Ncols;
                 if (MODE <= 1) {
                     bool ok = kk < g.Kred && n < g.Ncols;
-                    int off = ok ? rowoff + n : 0;
-                    uint4 v = ld16(a.Bw + off);
-                    if (!ok) v = make_uint4(0, 0, 0, 0);
-                    rb[i] = v;
+                    rb[i] = ld16(ok ? a.Bw + (rowoff + n) : zero_src);
                 } else {
                     unsigned short h16[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         bool ok = kk < g.Kred && (n + e) < g.Ncols;
-                        int off = ok ? rowoff + n + e : 0;
-                        unsigned short v = a.Bw[off];
-                        h16[e] = ok ? v : (unsigned short)0;
+                        h16[e] = *(ok ? a.Bw + (rowoff + n + e) : zero_src);
                     }
                     rb[i] = pack8(h16);
                 }
@@ -231,10 +229,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const KAr
         unsigned char* sB = sA + A_BYTES;
 #pragma unroll
         for (int i = 0; i < A_PASSES; ++i)
-            *reinterpret_cast<uint4*>(sA + (a_row0 + i * A_RPP) * A_PITCH + a_vec * 16) = ra[i];
+            *reinterpret_cast<u32x4*>(sA + (a_row0 + i * A_RPP) * A_PITCH + a_vec * 16) = ra[i];
 #pragma unroll
         for (int i = 0; i < B_PASSES; ++i)
-            *reinterpret_cast<uint4*>(sB + (b_row0 + i * B_RPP) * B_PITCH + b_vec * 16) = rb[i];
+            *reinterpret_cast<u32x4*>(sB + (b_row0 + i * B_RPP) * B_PITCH + b_vec * 16) = rb[i];
     };
 
     f32x16 acc[FN][FM];
@@ -282,16 +280,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_kernel(const KAr
     };
 
     if (kt_begin < kt_end) {
-        load_global(kt_begin);
+        // Each work-group starts its walk over the reduction tiles at a different offset (and wraps):
+        // work-groups running at the same time then read different channel slices and filter taps,
+        // which spreads their requests over the L2 channels instead of hammering the same few.
+        const int nkt = kt_end - kt_begin;
+        int cur = kt_begin + (int)(((unsigned)blockIdx.x / kNumXCD * 5u) % (unsigned)nkt);
+        load_global(cur);
         store_lds(0);
         __syncthreads();
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
-            const int stage = (kt - kt_begin) & 1;
-            const bool more = (kt + 1 < kt_end);
-            if (more) load_global(kt + 1);
+        for (int it = 0; it < nkt; ++it) {
+            const int stage = it & 1;
+            const bool more = (it + 1 < nkt);
+            int nxt = cur + 1;
+            if (nxt == kt_end) nxt = kt_begin;
+            if (more) load_global(nxt);
             compute(stage);
             if (more) store_lds(stage ^ 1);
             __syncthreads();
+            cur = nxt;
         }
     }
 
@@ -430,7 +436,7 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
 
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
-                    hipStream_t st) {
+                    hipStream_t st, hipEvent_t ev_mid) {
     KArgs ka;
     ka.A = A;
     ka.Bw = Bw;
@@ -472,6 +478,7 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
     }
 #undef WAP_DISPATCH
     if (rc != WAP_OK) return rc;
+    if (ev_mid) (void)hipEventRecord(ev_mid, st);
     if (ka.partial)
         return launch_reduce_bf16(reinterpret_cast<const float*>(ws), plan.nsplit,
                                   (size_t)g.M * g.Ncols, g.Ncols, bias, relu, out, st);

@@ -92,7 +92,7 @@ struct wap_step_plan {
 
 namespace {
 
-int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_t st) {
+int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_t st, hipEvent_t ev_mid = nullptr) {
     void* ws = base + p->ws_off;
     switch (op.kind) {
         case OP_CONV_FWD:
@@ -100,11 +100,11 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
         case OP_CONV_DGRAD:
         case OP_FC_DX:
             return launch_fwd_like(op.gg, op.b_tr, op.gp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
-                                   nullptr, op.relu, (bf16_t*)(base + op.t2), ws, st);
+                                   nullptr, op.relu, (bf16_t*)(base + op.t2), ws, st, ev_mid);
         case OP_CONV_WGRAD:
         case OP_FC_DW:
             return launch_wgrad(op.wg, op.wp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
-                                (float*)(base + op.t2), ws, st);
+                                (float*)(base + op.t2), ws, st, ev_mid);
         case OP_POOL_FWD:
             return launch_maxpool_fwd(op.N, op.H, op.W, op.C, op.win, op.st, (const bf16_t*)(base + op.t0),
                                       (bf16_t*)(base + op.t1), (uint8_t*)(base + op.t2), st);
@@ -438,38 +438,54 @@ int wap_step_op_info(const wap_step_plan* p, int32_t index, const char** name, c
 }
 
 int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
-                  float* us_out) {
+                  float* us_out, float* us_epilogue_out) {
     int rc = check_arena(p, arena, arena_bytes);
     if (rc != WAP_OK) return rc;
-    if (!us_out || steps < 1) return set_error(WAP_EINVAL, "step: bad argument");
+    if (!us_out || !us_epilogue_out || steps < 1) return set_error(WAP_EINVAL, "step: bad argument");
     unsigned char* base = (unsigned char*)arena;
     hipStream_t st = (hipStream_t)stream;
     const size_t n = p->ops.size();
-    const size_t need = 2 * n * (size_t)steps;
+    const size_t need = 3 * n * (size_t)steps;
     while (p->events.size() < need) {
         hipEvent_t e;
         if (hipEventCreate(&e) != hipSuccess) return set_error(WAP_EHIP, "hipEventCreate failed");
         p->events.push_back(e);
     }
+    auto has_epilogue = [&](const Op& op) {
+        switch (op.kind) {
+            case OP_CONV_FWD: case OP_FC_FWD: case OP_CONV_DGRAD: case OP_FC_DX: return op.gp.nsplit > 1;
+            case OP_CONV_WGRAD: case OP_FC_DW: return op.wp.nsplit > 1;
+            default: return false;
+        }
+    };
     for (int s = 0; s < steps && rc == WAP_OK; ++s)
         for (size_t i = 0; i < n && rc == WAP_OK; ++i) {
-            hipEvent_t* ev = &p->events[2 * ((size_t)s * n + i)];
+            hipEvent_t* ev = &p->events[3 * ((size_t)s * n + i)];
             (void)hipEventRecord(ev[0], st);
-            rc = run_op(p, p->ops[i], base, st);
+            rc = run_op(p, p->ops[i], base, st, has_epilogue(p->ops[i]) ? ev[2] : nullptr);
             (void)hipEventRecord(ev[1], st);
         }
     hipError_t e = hipStreamSynchronize(st);
     if (rc == WAP_OK && e != hipSuccess) rc = set_error(WAP_EHIP, "step: %s", hipGetErrorString(e));
     if (rc != WAP_OK) return rc;
     for (size_t i = 0; i < n; ++i) {
-        double sum = 0;
+        double sum = 0, sum_epi = 0;
+        const bool epi = has_epilogue(p->ops[i]);
         for (int s = 0; s < steps; ++s) {
             float ms = 0.f;
-            hipEvent_t* ev = &p->events[2 * ((size_t)s * n + i)];
-            (void)hipEventElapsedTime(&ms, ev[0], ev[1]);
-            sum += ms;
+            hipEvent_t* ev = &p->events[3 * ((size_t)s * n + i)];
+            if (epi) {
+                (void)hipEventElapsedTime(&ms, ev[0], ev[2]);
+                sum += ms;
+                (void)hipEventElapsedTime(&ms, ev[2], ev[1]);
+                sum_epi += ms;
+            } else {
+                (void)hipEventElapsedTime(&ms, ev[0], ev[1]);
+                sum += ms;
+            }
         }
         us_out[i] = (float)(sum * 1000.0 / steps);
+        us_epilogue_out[i] = (float)(sum_epi * 1000.0 / steps);
     }
     return WAP_OK;
 }

@@ -16,6 +16,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // one 16-byte load/store as an SSA value
 
 constexpr double kPeakBf16Tflops = 2516.6;  // 256 CU x 4096 FLOP/clk x 2.4 GHz
 constexpr double kPeakHbmGBs = 8000.0;
@@ -56,7 +57,7 @@ struct GemmPlan {
 GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr);
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
-                    hipStream_t st);
+                    hipStream_t st, hipEvent_t ev_mid = nullptr);  // ev_mid: recorded between kernel and split epilogue
 
 // Weight-gradient product: dw[k][(r,s,c)] = sum over pixels of dy[pix][k] * x[pix @ (r,s)][c].
 struct WgradGeom {
@@ -69,7 +70,7 @@ struct WgradPlan {
 };
 WgradPlan plan_wgrad(const WgradGeom& g);
 int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
-                 float* dw, void* ws, hipStream_t st);
+                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid = nullptr);
 
 const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan);
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan);

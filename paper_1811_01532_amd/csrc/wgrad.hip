@@ -52,10 +52,16 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
     return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
-__device__ __forceinline__ uint4 pack8(const unsigned short* h) {
-    return make_uint4((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16),
-                      (unsigned)h[4] | ((unsigned)h[5] << 16), (unsigned)h[6] | ((unsigned)h[7] << 16));
+// Masked-out elements load from this zero block (no select after the load, see igemm.hip).
+__device__ __align__(16) unsigned int g_zero_block_w[4] = {0u, 0u, 0u, 0u};
+
+__device__ __forceinline__ u32x4 pack8(const unsigned short* h) {
+    u32x4 v = {(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16),
+               (unsigned)h[4] | ((unsigned)h[5] << 16), (unsigned)h[6] | ((unsigned)h[7] << 16)};
+    return v;
 }
+
+__device__ __forceinline__ u32x4 ld16(const bf16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
 
 __device__ __forceinline__ bf16x8 tr_frag(const unsigned char* tile, int pitch, int colbase, int ks, int lane) {
     int col = colbase + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
@@ -119,7 +125,8 @@ __global__ __launch_bounds__(64 * WAVES_C * WAVES_K) void wgrad_kernel(const WAr
     }
     const int ko_d = ko0 + d_vec * 8;
 
-    uint4 rx[X_PASSES], rd[D_PASSES];
+    u32x4 rx[X_PASSES], rd[D_PASSES];
+    const bf16_t* zero_src = reinterpret_cast<const bf16_t*>(g_zero_block_w);
 
     auto load_global = [&](int kt) {
         const int pix0 = kt * BK;
@@ -137,19 +144,16 @@ __global__ __launch_bounds__(64 * WAVES_C * WAVES_K) void wgrad_kernel(const WAr
             if (MODE == 0) {
                 int h = hb + xr[0], w = wb + xs[0];
                 bool ok = pok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-                int off = ok ? base + (h * g.W + w) * g.C + xc[0] : 0;
-                uint4 v = *reinterpret_cast<const uint4*>(a.x + off);
-                if (!ok) v = make_uint4(0, 0, 0, 0);
-                rx[i] = v;
+                int off = base + (h * g.W + w) * g.C + xc[0];
+                rx[i] = ld16(ok ? a.x + off : zero_src);
             } else {
                 unsigned short h16[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     int h = hb + xr[e], w = wb + xs[e];
                     bool ok = pok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-                    int off = ok ? base + (h * g.W + w) * g.C + xc[e] : 0;
-                    unsigned short v = a.x[off];
-                    h16[e] = ok ? v : (unsigned short)0;
+                    int off = base + (h * g.W + w) * g.C + xc[e];
+                    h16[e] = *(ok ? a.x + off : zero_src);
                 }
                 rx[i] = pack8(h16);
             }
@@ -160,18 +164,13 @@ __global__ __launch_bounds__(64 * WAVES_C * WAVES_K) void wgrad_kernel(const WAr
             bool pok = pix < a.Mred;
             if (MODE == 0) {
                 bool ok = pok && ko_d < g.K;
-                size_t off = ok ? (size_t)pix * g.K + ko_d : 0;
-                uint4 v = *reinterpret_cast<const uint4*>(a.dy + off);
-                if (!ok) v = make_uint4(0, 0, 0, 0);
-                rd[i] = v;
+                rd[i] = ld16(ok ? a.dy + ((size_t)pix * g.K + ko_d) : zero_src);
             } else {
                 unsigned short h16[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     bool ok = pok && (ko_d + e) < g.K;
-                    size_t off = ok ? (size_t)pix * g.K + ko_d + e : 0;
-                    unsigned short v = a.dy[off];
-                    h16[e] = ok ? v : (unsigned short)0;
+                    h16[e] = *(ok ? a.dy + ((size_t)pix * g.K + ko_d + e) : zero_src);
                 }
                 rd[i] = pack8(h16);
             }
@@ -183,10 +182,10 @@ __global__ __launch_bounds__(64 * WAVES_C * WAVES_K) void wgrad_kernel(const WAr
         unsigned char* sD = sX + X_BYTES;
 #pragma unroll
         for (int i = 0; i < X_PASSES; ++i)
-            *reinterpret_cast<uint4*>(sX + (x_row0 + i * X_RPP) * X_PITCH + x_vec * 16) = rx[i];
+            *reinterpret_cast<u32x4*>(sX + (x_row0 + i * X_RPP) * X_PITCH + x_vec * 16) = rx[i];
 #pragma unroll
         for (int i = 0; i < D_PASSES; ++i)
-            *reinterpret_cast<uint4*>(sD + (d_row0 + i * D_RPP) * D_PITCH + d_vec * 16) = rd[i];
+            *reinterpret_cast<u32x4*>(sD + (d_row0 + i * D_RPP) * D_PITCH + d_vec * 16) = rd[i];
     };
 
     f32x16 acc[FC][FK];
@@ -315,7 +314,7 @@ WgradPlan plan_wgrad(const WgradGeom& g) {
 }
 
 int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
-                 float* dw, void* ws, hipStream_t st) {
+                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid) {
     WArgs wa;
     wa.x = x;
     wa.dy = dy;
@@ -344,6 +343,7 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
         rc = launch_one<256, 64, 4, 1, 0>(wa, smem, st);
     }
     if (rc != WAP_OK) return rc;
+    if (ev_mid) (void)hipEventRecord(ev_mid, st);
     if (plan.nsplit > 1)
         return launch_reduce_f32(reinterpret_cast<const float*>(ws), plan.nsplit,
                                  (size_t)g.K * wa.Kred, dw, st);
