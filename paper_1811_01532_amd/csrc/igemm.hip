@@ -362,6 +362,8 @@ constexpr Cfg kCfgs[] = {
     {128, 128, 256},  // 1: medium / general
     {64, 256, 256},   // 2: few rows (small-batch FC)
     {256, 64, 256},   // 3: few output channels
+    {256, 256, 256},  // 4: large, 4 wavefronts of 128x128 (less LDS traffic per MFMA)
+    {256, 256, 256},  // 5: large, weights in registers (conv_wreg.hip)
 };
 
 size_t smem_bytes(const Cfg& c, bool b_tr) {
@@ -410,11 +412,11 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
     } else if (g.M <= 64) {
         cfg = 2;
     } else if (tiles(0) >= 200 && g.Ncols >= 192) {
-        cfg = 0;
+        cfg = wreg_supported(g) ? 5 : 0;
     } else {
         cfg = 1;
     }
-    if (g_force_fwd_cfg >= 0 && g_force_fwd_cfg < 4 && (mode == 0 || g_force_fwd_cfg == 1)) cfg = g_force_fwd_cfg;
+    if (g_force_fwd_cfg >= 0 && g_force_fwd_cfg < 6 && (mode == 0 || g_force_fwd_cfg == 1)) cfg = g_force_fwd_cfg;
     long t = tiles(cfg);
     int nsplit = 1;
     // split the reduction when the tiles alone leave most CUs idle
@@ -428,9 +430,11 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
     if (g_force_nsplit >= 1) nsplit = g_force_nsplit < ktiles ? g_force_nsplit : ktiles;
     int kps = (ktiles + nsplit - 1) / nsplit;
     nsplit = (ktiles + kps - 1) / kps;
+    if (cfg == 5 && !wreg_supported(g)) cfg = 0;
     p.cfg = cfg;
     p.nsplit = nsplit;
     p.ws_bytes = nsplit > 1 ? (size_t)nsplit * g.M * g.Ncols * sizeof(float) : 0;
+    if (cfg == 5) p.ws_bytes += wreg_wt_bytes(g);  // weights repacked into MFMA fragment order
     return p;
 }
 
@@ -451,6 +455,21 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
     ka.bias = ka.partial ? nullptr : bias;
     ka.relu = ka.partial ? 0 : (relu ? 1 : 0);
     ka.out = ka.partial ? ws : (void*)out;
+    if (plan.cfg == 5) {
+        // the (small) weight tensor is first repacked into MFMA fragment order (taps flipped and
+        // transposed for the data gradient); the partial tiles, if any, follow it in the workspace
+        int rc0 = launch_pack_weights(g, b_tr, Bw, ws, st);
+        if (rc0 != WAP_OK) return rc0;
+        void* part = reinterpret_cast<unsigned char*>(ws) + wreg_wt_bytes(g);
+        int rc5 = launch_wreg(g, plan.nsplit, A, reinterpret_cast<const bf16_t*>(ws), bias, relu,
+                              ka.partial ? part : (void*)out, ka.partial != 0, st);
+        if (rc5 != WAP_OK) return rc5;
+        if (ev_mid) (void)hipEventRecord(ev_mid, st);
+        if (ka.partial)
+            return launch_reduce_bf16(reinterpret_cast<const float*>(part), plan.nsplit, (size_t)g.M * g.Ncols,
+                                      g.Ncols, bias, relu, out, st);
+        return WAP_OK;
+    }
     size_t smem = smem_bytes(c, b_tr);
     int mode = classify_mode(g, b_tr);
     int rc;
@@ -465,6 +484,10 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
         if (mode != 0) return set_error(WAP_EINVAL, "internal: large tile needs the fast mode");
         rc = b_tr ? launch_one<256, 256, 2, 4, true, 0>(ka, smem, st)
                   : launch_one<256, 256, 2, 4, false, 0>(ka, smem, st);
+    } else if (plan.cfg == 4) {
+        if (mode != 0) return set_error(WAP_EINVAL, "internal: large tile needs the fast mode");
+        rc = b_tr ? launch_one<256, 256, 2, 2, true, 0>(ka, smem, st)
+                  : launch_one<256, 256, 2, 2, false, 0>(ka, smem, st);
     } else if (plan.cfg == 1) {
         rc = WAP_DISPATCH(128, 128, 2, 2);
     } else if (plan.cfg == 2) {
@@ -490,12 +513,14 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
 namespace wap {
 // Label of the kernel instantiation a plan launches (matches the demangled kernel name).
 const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan) {
-    static const char* names[4][2][3] = {
+    if (plan.cfg == 5) return "conv_wreg_kernel";
+    static const char* names[5][2][3] = {
         {{"igemm_kernel<256,256,2,4,false,0>", "", ""}, {"igemm_kernel<256,256,2,4,true,0>", "", ""}},
         {{"igemm_kernel<128,128,2,2,false,0>", "igemm_kernel<128,128,2,2,false,1>", "igemm_kernel<128,128,2,2,false,2>"},
          {"igemm_kernel<128,128,2,2,true,0>", "igemm_kernel<128,128,2,2,true,1>", "igemm_kernel<128,128,2,2,true,2>"}},
         {{"igemm_kernel<64,256,1,4,false,0>", "", ""}, {"igemm_kernel<64,256,1,4,true,0>", "", ""}},
         {{"igemm_kernel<256,64,4,1,false,0>", "", ""}, {"igemm_kernel<256,64,4,1,true,0>", "", ""}},
+        {{"igemm_kernel<256,256,2,2,false,0>", "", ""}, {"igemm_kernel<256,256,2,2,true,0>", "", ""}},
     };
     return names[plan.cfg][b_tr ? 1 : 0][classify_mode(g, b_tr)];
 }

@@ -72,6 +72,13 @@ WgradPlan plan_wgrad(const WgradGeom& g);
 int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
                  float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid = nullptr);
 
+// weights-in-registers large-tile kernel (conv_wreg.hip)
+bool wreg_supported(const GemmGeom& g);
+inline size_t wreg_wt_bytes(const GemmGeom& g) { return (size_t)((g.Ncols + 31) / 32) * 32 * g.Kred * 2; }  // packed copy
+int launch_pack_weights(const GemmGeom& g, bool flip, const bf16_t* w, void* Wp, hipStream_t st);
+int launch_wreg(const GemmGeom& g, int nsplit, const bf16_t* A, const bf16_t* Bw, const float* bias, bool relu,
+                void* out, bool partial, hipStream_t st);
+
 const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan);
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan);
 
