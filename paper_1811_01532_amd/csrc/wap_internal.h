@@ -79,6 +79,11 @@ int launch_pack_weights(const GemmGeom& g, bool flip, const bf16_t* w, void* Wp,
 int launch_wreg(const GemmGeom& g, int nsplit, const bf16_t* A, const bf16_t* Bw, const float* bias, bool relu,
                 void* out, bool partial, hipStream_t st);
 
+// stride-1 convolution with the input patch resident in LDS (conv_patch.hip)
+int patch_supported(const GemmGeom& g);
+int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
+                 hipStream_t st);
+
 const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan);
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan);
 
