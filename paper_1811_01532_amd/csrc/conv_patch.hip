@@ -37,6 +37,7 @@ struct PArgs {
     int patch_cap;     // LDS rows per patch buffer
     int relu;
     unsigned a_bytes, w_bytes;
+    FastDiv dOHW, dOW, dPHW, dPW;
 };
 
 __device__ __forceinline__ int xcd_remap(int bid, int total) {
@@ -74,9 +75,9 @@ __global__ __launch_bounds__(NT) void conv_patch_kernel(const PArgs a) {
 
     // padded-flat index of output pixel m (tap (0,0)): ((n * PH + oh) * PW + ow)
     auto pflat = [&](int m) {
-        int n = m / OHW;
+        int n = (int)fdiv((uint32_t)m, a.dOHW);
         int rem = m - n * OHW;
-        int oh = rem / g.OW;
+        int oh = (int)fdiv((uint32_t)rem, a.dOW);
         int ow = rem - oh * g.OW;
         return n * PHW + oh * PW + ow;
     };
@@ -93,9 +94,9 @@ __global__ __launch_bounds__(NT) void conv_patch_kernel(const PArgs a) {
         unsigned off = OOB;
         if (q < patch_len) {
             int p = p_lo + q;
-            int n = p / PHW;
+            int n = (int)fdiv((uint32_t)p, a.dPHW);
             int rem = p - n * PHW;
-            int vh = rem / PW;
+            int vh = (int)fdiv((uint32_t)rem, a.dPW);
             int vw = rem - vh * PW;
             int ih = vh - g.pad_h, iw = vw - g.pad_w;
             if (n * OHW < g.M && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW)
@@ -214,7 +215,53 @@ __global__ __launch_bounds__(NT) void conv_patch_kernel(const PArgs a) {
         __syncthreads();
     }
 
-    // ---- epilogue: lane holds 4 consecutive channels of one pixel per register quad ----
+    // ---- epilogue.  A lane holds 4 consecutive channels of one pixel per register quad; when the channel
+    // count allows 16-byte rows the tile is transposed through LDS (free after the last slice) in two
+    // pixel halves so that every global store is a full, contiguous 16 bytes per lane. ----
+    if ((g.Ncols & 7) == 0) {
+        constexpr int OPITCH = BN * 2 + 16;  // bytes per pixel row in the staging buffer
+        constexpr int VPR = BN / 8;          // 16-byte vectors per pixel row
+        constexpr int RPP = NT / VPR;        // pixel rows stored per pass
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int j0 = half * 4, j1 = half ? FM : 4;
+            __syncthreads();  // previous readers of the staging area (or of the patch) are done
+#pragma unroll
+            for (int j = j0; j < j1; ++j)
+#pragma unroll
+                for (int i = 0; i < FN; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int nl = wave * 32 * FN + i * 32 + q * 8 + (lane >> 5) * 4;  // channel within the tile
+                        float v[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
+                        if (a.bias) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (n0 + nl + e < g.Ncols) v[e] += a.bias[n0 + nl + e];
+                        }
+                        if (a.relu) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+                        }
+                        uint2 pk = make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16),
+                                              (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+                        *reinterpret_cast<uint2*>(smem + ((j - j0) * 32 + (lane & 31)) * OPITCH + nl * 2) = pk;
+                    }
+            __syncthreads();
+            const int rows = (j1 - j0) * 32;
+            for (int row = tid / VPR; row < rows; row += RPP) {
+                const int m = m0 + j0 * 32 + row;
+                const int n = n0 + (tid % VPR) * 8;
+                if (m <= m_last && n < g.Ncols) {
+                    u32x4 vv = *reinterpret_cast<const u32x4*>(smem + row * OPITCH + (tid % VPR) * 16);
+                    *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.out) + (size_t)m * g.Ncols + n) = vv;
+                }
+            }
+        }
+        return;
+    }
     const bool vec4 = (g.Ncols & 3) == 0;
 #pragma unroll
     for (int j = 0; j < FM; ++j) {
@@ -315,6 +362,10 @@ int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float
     pa.patch_cap = patch_supported(g);
     if (!pa.patch_cap) return set_error(WAP_EINVAL, "internal: patch kernel not applicable");
     pa.relu = relu ? 1 : 0;
+    pa.dOHW = make_fastdiv((uint32_t)(g.OH * g.OW));
+    pa.dOW = make_fastdiv((uint32_t)g.OW);
+    pa.dPHW = make_fastdiv((uint32_t)(pa.PH * pa.PW));
+    pa.dPW = make_fastdiv((uint32_t)pa.PW);
     pa.a_bytes = (unsigned)((size_t)(g.M / (g.OH * g.OW)) * g.IH * g.IW * g.IC * 2);
     pa.w_bytes = (unsigned)wreg_wt_bytes(g);
     pa.tiles_m = (g.M + BM - 1) / BM;

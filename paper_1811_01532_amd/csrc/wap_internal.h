@@ -18,6 +18,20 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // one 16-byte load/store as an SSA value
 
+// exact floor(x / d) for 0 <= x < 2^31 by multiply-high and shift (d >= 1)
+struct FastDiv {
+    uint32_t mul, shift;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    uint32_t sh = 0;
+    while ((1ull << sh) < d) ++sh;
+    f.shift = sh;
+    f.mul = (uint32_t)((((1ull << 32) * ((1ull << sh) - d)) / d) + 1);
+    return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t x, FastDiv f) { return (__umulhi(x, f.mul) + x) >> f.shift; }
+
 constexpr double kPeakBf16Tflops = 2516.6;  // 256 CU x 4096 FLOP/clk x 2.4 GHz
 constexpr double kPeakHbmGBs = 8000.0;
 constexpr int kNumCU = 256;

@@ -18,24 +18,6 @@ namespace {
 
 constexpr int BK = 64;  // pixels per reduction tile
 
-struct FastDiv {
-    uint32_t mul, shift;
-};
-
-FastDiv make_fastdiv(uint32_t d) {
-    FastDiv f;
-    uint32_t sh = 0;
-    while ((1ull << sh) < d) ++sh;
-    f.shift = sh;
-    f.mul = (uint32_t)((((1ull << 32) * ((1ull << sh) - d)) / d) + 1);
-    return f;
-}
-
-// exact floor(x / d) for 0 <= x < 2^31
-__device__ __forceinline__ uint32_t fdiv(uint32_t x, FastDiv f) {
-    return (__umulhi(x, f.mul) + x) >> f.shift;
-}
-
 struct WArgs {
     const bf16_t* x;
     const bf16_t* dy;
