@@ -365,6 +365,7 @@ constexpr Cfg kCfgs[] = {
     {256, 256, 256},  // 4: large, 4 wavefronts of 128x128 (less LDS traffic per MFMA)
     {256, 256, 256},  // 5: large, weights in registers (conv_wreg.hip)
     {224, 256, 256},  // 6: stride-1 multi-tap conv, input patch in LDS (conv_patch.hip)
+    {256, 64, 256},   // 7: stride-1 multi-tap conv, 8 x 32-pixel tiles, 64 / 128 channels (conv_tile2d.hip)
 };
 
 size_t smem_bytes(const Cfg& c, bool b_tr) {
@@ -417,7 +418,7 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
     } else {
         cfg = 1;
     }
-    if (g_force_fwd_cfg >= 0 && g_force_fwd_cfg < 7 && (mode == 0 || g_force_fwd_cfg == 1)) cfg = g_force_fwd_cfg;
+    if (g_force_fwd_cfg >= 0 && g_force_fwd_cfg < 8 && (mode == 0 || g_force_fwd_cfg == 1)) cfg = g_force_fwd_cfg;
     long t = tiles(cfg);
     int nsplit = 1;
     // split the reduction when the tiles alone leave most CUs idle
@@ -434,11 +435,13 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
     if (cfg == 5 && !wreg_supported(g)) cfg = 0;
     if (g_force_fwd_cfg < 0 && patch_supported(g)) cfg = 6;
     if (cfg == 6 && !patch_supported(g)) cfg = 1;
-    if (cfg == 6) nsplit = 1;
+    if (g_force_fwd_cfg < 0 && g.Ncols <= 128 && tile2d_supported(g)) cfg = 7;
+    if (cfg == 7 && !tile2d_supported(g)) cfg = 1;
+    if (cfg == 6 || cfg == 7) nsplit = 1;
     p.cfg = cfg;
     p.nsplit = nsplit;
     p.ws_bytes = nsplit > 1 ? (size_t)nsplit * g.M * g.Ncols * sizeof(float) : 0;
-    if (cfg == 5 || cfg == 6) p.ws_bytes += wreg_wt_bytes(g);  // weights repacked into MFMA fragment order
+    if (cfg >= 5) p.ws_bytes += wreg_wt_bytes(g);  // weights repacked into MFMA fragment order
     return p;
 }
 
@@ -449,7 +452,7 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
     ka.A = A;
     ka.Bw = Bw;
     ka.g = g;
-    const Cfg& c = kCfgs[plan.cfg];
+    const Cfg& c = kCfgs[plan.cfg < 5 ? plan.cfg : 0];
     ka.tiles_m = (g.M + c.BM - 1) / c.BM;
     ka.tiles_n = (g.Ncols + c.BN - 1) / c.BN;
     ka.ktiles = (g.Kred + BK - 1) / BK;
@@ -459,10 +462,11 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
     ka.bias = ka.partial ? nullptr : bias;
     ka.relu = ka.partial ? 0 : (relu ? 1 : 0);
     ka.out = ka.partial ? ws : (void*)out;
-    if (plan.cfg == 6) {
+    if (plan.cfg == 6 || plan.cfg == 7) {
         int rc0 = launch_pack_weights(g, b_tr, Bw, ws, st);
         if (rc0 != WAP_OK) return rc0;
-        return launch_patch(g, A, ws, bias, relu, out, st);
+        return plan.cfg == 6 ? launch_patch(g, A, ws, bias, relu, out, st)
+                             : launch_tile2d(g, A, ws, bias, relu, out, st);
     }
     if (plan.cfg == 5) {
         // the (small) weight tensor is first repacked into MFMA fragment order (taps flipped and
@@ -524,6 +528,7 @@ namespace wap {
 const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan) {
     if (plan.cfg == 5) return "conv_wreg_kernel";
     if (plan.cfg == 6) return "conv_patch_kernel";
+    if (plan.cfg == 7) return "conv_tile2d_kernel";
     static const char* names[5][2][3] = {
         {{"igemm_kernel<256,256,2,4,false,0>", "", ""}, {"igemm_kernel<256,256,2,4,true,0>", "", ""}},
         {{"igemm_kernel<128,128,2,2,false,0>", "igemm_kernel<128,128,2,2,false,1>", "igemm_kernel<128,128,2,2,false,2>"},

@@ -98,6 +98,11 @@ int patch_supported(const GemmGeom& g);
 int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
                  hipStream_t st);
 
+// stride-1 convolution on 8 x 32-pixel 2-D tiles for 64 / 128 output channels (conv_tile2d.hip)
+int tile2d_supported(const GemmGeom& g);
+int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
+                  hipStream_t st);
+
 const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan);
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan);
 

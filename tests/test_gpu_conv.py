@@ -29,6 +29,18 @@ CASES = [
     ("odd_everything", (1, 7, 9, 5, 7, 3, 2, 1, 1), (-1, -1, -1)),
     ("k_not_multiple_of_4", (1, 6, 6, 8, 10, 3, 3, 1, 1), (-1, -1, -1)),
     ("rect_filter_stride_2_1", (1, 15, 12, 16, 24, 4, 3, (2, 1), (1, 0)), (-1, -1, -1)),
+    # weights-in-registers kernel (ragged rows and columns, stride 2 forward, split reduction)
+    ("wreg_forced_ragged", (2, 21, 23, 64, 200, 3, 3, 1, 1), (5, -1, -1)),
+    ("wreg_forced_stride2_split2", (1, 30, 30, 128, 96, 3, 3, 2, 1), (5, -1, 2)),
+    # patch-in-LDS kernel: chosen from the shape; ragged last tile, one and two channel slices, both widths
+    ("patch_auto_k128_ragged", (2, 88, 88, 64, 128, 3, 3, 1, 1), (-1, -1, -1)),
+    ("patch_auto_k256_two_slices", (1, 120, 121, 128, 256, 3, 3, 1, 1), (-1, -1, -1)),
+    # 8 x 32-pixel 2-D tile kernel: chosen from the shape for 64 channels, forced for 128
+    ("tile2d_auto_c64_k64", (2, 16, 64, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
+    ("tile2d_auto_c128_k64_3x2", (1, 24, 33, 128, 64, 3, 2, 1, (1, 0)), (-1, -1, -1)),
+    ("tile2d_forced_c128_k128", (1, 24, 32, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
+    ("tile2d_auto_square_tiles_c64_k64", (2, 32, 48, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
+    ("tile2d_forced_square_tiles_c128_k128", (1, 16, 48, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
 ]
 
 
