@@ -82,6 +82,46 @@ __global__ void reduce_f32_kernel(const float* __restrict__ part, int nsplit, si
     }
 }
 
+// Many splits of a small tensor: G groups of threads each add the splits k = g, g + G, g + 2G, ... of one
+// 16-byte column in increasing k (four independent loads in flight), then the G partial sums are added in
+// group order through LDS.  The summation tree is fixed by (nsplit, G), so results are bitwise reproducible.
+template <int G>
+__global__ __launch_bounds__(256) void reduce_f32_grouped_kernel(const float* __restrict__ part, int nsplit, size_t elems,
+                                                               float* __restrict__ out) {
+    constexpr int COLS = 256 / G;
+    __shared__ float4 sm[G][COLS];
+    const int col = threadIdx.x % COLS, grp = threadIdx.x / COLS;
+    const size_t n4 = elems / 4;
+    const size_t i = (size_t)blockIdx.x * COLS + col;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n4) {
+        const float4* p = reinterpret_cast<const float4*>(part) + i;
+        int k = grp;
+        for (; k + 3 * G < nsplit; k += 4 * G) {
+            float4 t0 = p[(size_t)k * n4], t1 = p[(size_t)(k + G) * n4], t2 = p[(size_t)(k + 2 * G) * n4],
+                   t3 = p[(size_t)(k + 3 * G) * n4];
+            s.x += t0.x; s.y += t0.y; s.z += t0.z; s.w += t0.w;
+            s.x += t1.x; s.y += t1.y; s.z += t1.z; s.w += t1.w;
+            s.x += t2.x; s.y += t2.y; s.z += t2.z; s.w += t2.w;
+            s.x += t3.x; s.y += t3.y; s.z += t3.z; s.w += t3.w;
+        }
+        for (; k < nsplit; k += G) {
+            float4 t = p[(size_t)k * n4];
+            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+    }
+    sm[grp][col] = s;
+    __syncthreads();
+    if (grp == 0 && i < n4) {
+#pragma unroll
+        for (int g2 = 1; g2 < G; ++g2) {
+            float4 t = sm[g2][col];
+            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+        reinterpret_cast<float4*>(out)[i] = s;
+    }
+}
+
 // ---- ReLU backward ----
 __global__ void relu_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ y,
                                 bf16_t* dx, size_t n) {
@@ -329,6 +369,17 @@ int launch_reduce_bf16(const float* part, int nsplit, size_t elems, int ncols, c
 }
 
 int launch_reduce_f32(const float* part, int nsplit, size_t elems, float* out, hipStream_t st) {
+    if ((elems & 3) == 0 && nsplit >= 8) {
+        const size_t n4 = elems / 4;
+        if (nsplit >= 64) {
+            hipLaunchKernelGGL(reduce_f32_grouped_kernel<32>, dim3((unsigned)((n4 + 7) / 8)), dim3(256), 0, st, part, nsplit,
+                               elems, out);
+        } else {
+            hipLaunchKernelGGL(reduce_f32_grouped_kernel<8>, dim3((unsigned)((n4 + 31) / 32)), dim3(256), 0, st, part, nsplit,
+                               elems, out);
+        }
+        return check_launch("reduce_f32_grouped");
+    }
     hipLaunchKernelGGL(reduce_f32_kernel, dim3(grid_for(elems / 4 + 1)), dim3(kThreads), 0, st, part,
                        nsplit, elems, out);
     return check_launch("reduce_f32");

@@ -86,6 +86,11 @@ WgradPlan plan_wgrad(const WgradGeom& g);
 int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
                  float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid = nullptr);
 
+// stride-1 3x3 weight gradient with the input patch resident in LDS (wgrad_patch.hip)
+bool wgrad_patch_supported(const WgradGeom& g);
+int wgrad_patch_nsplit(const WgradGeom& g);
+int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* out, hipStream_t st);
+
 // weights-in-registers large-tile kernel (conv_wreg.hip)
 bool wreg_supported(const GemmGeom& g);
 inline size_t wreg_wt_bytes(const GemmGeom& g) { return (size_t)((g.Ncols + 31) / 32) * 32 * g.Kred * 2; }  // packed copy

@@ -277,6 +277,14 @@ WgradPlan plan_wgrad(const WgradGeom& g) {
     else if (g.K >= 192 && Kred >= 256) cfg = 0;
     else cfg = 1;
     if (g_force_wgrad_cfg >= 0 && g_force_wgrad_cfg < 3 && (mode == 0 || g_force_wgrad_cfg == 1)) cfg = g_force_wgrad_cfg;
+    if ((g_force_wgrad_cfg < 0 || g_force_wgrad_cfg == 3) && mode == 0 && wgrad_patch_supported(g)) {
+        p.cfg = 3;
+        p.nsplit = g_force_nsplit >= 1 ? g_force_nsplit : wgrad_patch_nsplit(g);
+        long tiles_total = (long)g.N * g.P * g.Q / 64;  // every tile holds at least 64 pixels
+        if (p.nsplit > tiles_total) p.nsplit = (int)tiles_total;
+        p.ws_bytes = p.nsplit > 1 ? (size_t)p.nsplit * g.K * Kred * sizeof(float) : 0;
+        return p;
+    }
     const Cfg& c = kCfgs[cfg];
     long tiles = (long)((Kred + c.TC - 1) / c.TC) * ((g.K + c.TK - 1) / c.TK);
     int ktiles = (int)((Mred + BK - 1) / BK);
@@ -303,7 +311,7 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
     wa.g = g;
     wa.Kred = g.R * g.S * g.C;
     wa.Mred = g.N * g.P * g.Q;
-    const Cfg& c = kCfgs[plan.cfg];
+    const Cfg& c = kCfgs[plan.cfg < 3 ? plan.cfg : 0];
     wa.tiles_c = (wa.Kred + c.TC - 1) / c.TC;
     wa.tiles_k = (g.K + c.TK - 1) / c.TK;
     wa.ktiles = (wa.Mred + BK - 1) / BK;
@@ -312,6 +320,14 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
     wa.dPQ = make_fastdiv((uint32_t)(g.P * g.Q));
     wa.dQ = make_fastdiv((uint32_t)g.Q);
     wa.out = plan.nsplit > 1 ? reinterpret_cast<float*>(ws) : dw;
+    if (plan.cfg == 3) {
+        int rc3 = launch_wgrad_patch(g, plan.nsplit, x, dy, wa.out, st);
+        if (rc3 != WAP_OK) return rc3;
+        if (ev_mid) (void)hipEventRecord(ev_mid, st);
+        if (plan.nsplit > 1)
+            return launch_reduce_f32(reinterpret_cast<const float*>(ws), plan.nsplit, (size_t)g.K * wa.Kred, dw, st);
+        return WAP_OK;
+    }
     size_t smem = smem_bytes(c);
     int mode = classify_mode(g);
     int rc;
@@ -336,6 +352,7 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
 
 namespace wap {
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan) {
+    if (plan.cfg == 3) return "wgrad_patch_kernel";
     static const char* names[3][2] = {
         {"wgrad_kernel<256,256,2,4,0>", ""},
         {"wgrad_kernel<128,128,2,2,0>", "wgrad_kernel<128,128,2,2,1>"},

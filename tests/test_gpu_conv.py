@@ -41,6 +41,10 @@ CASES = [
     ("tile2d_forced_c128_k128", (1, 24, 32, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
     ("tile2d_auto_square_tiles_c64_k64", (2, 32, 48, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("tile2d_forced_square_tiles_c128_k128", (1, 16, 48, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
+    # patch-in-LDS weight gradient: masked surplus columns (14 -> 16), a forced uneven split, pad 0
+    ("wgrad_patch_w14_masked_columns", (3, 14, 14, 128, 64, 3, 3, 1, 1), (-1, -1, -1)),
+    ("wgrad_patch_w28_forced_split5", (1, 28, 28, 64, 128, 3, 3, 1, 1), (-1, 3, 5)),
+    ("wgrad_patch_pad0_w30", (2, 34, 32, 64, 64, 3, 3, 1, 0), (-1, -1, -1)),
 ]
 
 
