@@ -401,6 +401,12 @@ int classify_mode(const GemmGeom& g, bool b_tr) {
 
 GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
     GemmPlan p;
+    if (!b_tr && (g_force_fwd_cfg < 0 || g_force_fwd_cfg == 8) && conv_c3_fwd_supported(g)) {
+        p.cfg = 8;
+        p.nsplit = 1;
+        p.ws_bytes = 0;
+        return p;
+    }
     int mode = classify_mode(g, b_tr);
     int ktiles = (g.Kred + BK - 1) / BK;
     auto tiles = [&](int c) {
@@ -448,6 +454,7 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
                     hipStream_t st, hipEvent_t ev_mid) {
+    if (plan.cfg == 8) return launch_conv_c3_fwd(g, A, Bw, bias, relu, out, st);
     KArgs ka;
     ka.A = A;
     ka.Bw = Bw;
@@ -529,6 +536,7 @@ const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& p
     if (plan.cfg == 5) return "conv_wreg_kernel";
     if (plan.cfg == 6) return "conv_patch_kernel";
     if (plan.cfg == 7) return "conv_tile2d_kernel";
+    if (plan.cfg == 8) return "conv_c3_fwd_kernel";
     static const char* names[5][2][3] = {
         {{"igemm_kernel<256,256,2,4,false,0>", "", ""}, {"igemm_kernel<256,256,2,4,true,0>", "", ""}},
         {{"igemm_kernel<128,128,2,2,false,0>", "igemm_kernel<128,128,2,2,false,1>", "igemm_kernel<128,128,2,2,false,2>"},

@@ -91,6 +91,14 @@ bool wgrad_patch_supported(const WgradGeom& g);
 int wgrad_patch_nsplit(const WgradGeom& g);
 int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* out, hipStream_t st);
 
+// 3-input-channel 3x3 stride-1 first layer (conv_c3.hip)
+bool conv_c3_fwd_supported(const GemmGeom& g);
+int launch_conv_c3_fwd(const GemmGeom& g, const bf16_t* x, const bf16_t* w, const float* bias, bool relu, bf16_t* y,
+                       hipStream_t st);
+bool wgrad_c3_supported(const WgradGeom& g);
+int wgrad_c3_nsplit(const WgradGeom& g);
+int launch_wgrad_c3(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* part, hipStream_t st);
+
 // weights-in-registers large-tile kernel (conv_wreg.hip)
 bool wreg_supported(const GemmGeom& g);
 inline size_t wreg_wt_bytes(const GemmGeom& g) { return (size_t)((g.Ncols + 31) / 32) * 32 * g.Kred * 2; }  // packed copy

@@ -277,6 +277,12 @@ WgradPlan plan_wgrad(const WgradGeom& g) {
     else if (g.K >= 192 && Kred >= 256) cfg = 0;
     else cfg = 1;
     if (g_force_wgrad_cfg >= 0 && g_force_wgrad_cfg < 3 && (mode == 0 || g_force_wgrad_cfg == 1)) cfg = g_force_wgrad_cfg;
+    if ((g_force_wgrad_cfg < 0 || g_force_wgrad_cfg == 4) && wgrad_c3_supported(g)) {
+        p.cfg = 4;
+        p.nsplit = wgrad_c3_nsplit(g);
+        p.ws_bytes = (size_t)p.nsplit * g.K * Kred * sizeof(float);  // always reduced from per-work-group partials
+        return p;
+    }
     if ((g_force_wgrad_cfg < 0 || g_force_wgrad_cfg == 3) && mode == 0 && wgrad_patch_supported(g)) {
         p.cfg = 3;
         p.nsplit = g_force_nsplit >= 1 ? g_force_nsplit : wgrad_patch_nsplit(g);
@@ -320,6 +326,12 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
     wa.dPQ = make_fastdiv((uint32_t)(g.P * g.Q));
     wa.dQ = make_fastdiv((uint32_t)g.Q);
     wa.out = plan.nsplit > 1 ? reinterpret_cast<float*>(ws) : dw;
+    if (plan.cfg == 4) {
+        int rc4 = launch_wgrad_c3(g, plan.nsplit, x, dy, reinterpret_cast<float*>(ws), st);
+        if (rc4 != WAP_OK) return rc4;
+        if (ev_mid) (void)hipEventRecord(ev_mid, st);
+        return launch_reduce_f32(reinterpret_cast<const float*>(ws), plan.nsplit, (size_t)g.K * wa.Kred, dw, st);
+    }
     if (plan.cfg == 3) {
         int rc3 = launch_wgrad_patch(g, plan.nsplit, x, dy, wa.out, st);
         if (rc3 != WAP_OK) return rc3;
@@ -353,6 +365,7 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
 namespace wap {
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan) {
     if (plan.cfg == 3) return "wgrad_patch_kernel";
+    if (plan.cfg == 4) return "wgrad_c3_kernel";
     static const char* names[3][2] = {
         {"wgrad_kernel<256,256,2,4,0>", ""},
         {"wgrad_kernel<128,128,2,2,0>", "wgrad_kernel<128,128,2,2,1>"},

@@ -45,6 +45,10 @@ CASES = [
     ("wgrad_patch_w14_masked_columns", (3, 14, 14, 128, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("wgrad_patch_w28_forced_split5", (1, 28, 28, 64, 128, 3, 3, 1, 1), (-1, 3, 5)),
     ("wgrad_patch_pad0_w30", (2, 34, 32, 64, 64, 3, 3, 1, 0), (-1, -1, -1)),
+    # 3-input-channel first-layer kernels: ragged last tile / step, 32 and 64 output channels, pad 0
+    ("c3_k64_ragged", (3, 41, 40, 3, 64, 3, 3, 1, 1), (-1, -1, -1)),
+    ("c3_k32", (2, 48, 48, 3, 32, 3, 3, 1, 1), (-1, -1, -1)),
+    ("c3_k64_pad0", (2, 50, 50, 3, 64, 3, 3, 1, 0), (-1, -1, -1)),
 ]
 
 
