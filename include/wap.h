@@ -93,6 +93,13 @@ int wap_conv2d_fwd(const wap_conv_desc* d, const void* x, const void* w, const f
 int wap_conv2d_bwd_data(const wap_conv_desc* d, const void* dy, const void* w, void* dx,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* The same product followed by the ReLU derivative of the layer that produced x (the backward half of
+ * t_c, Eq. 1, of a conv whose input is another layer's ReLU output): dx = (x_act > 0) ? dx : 0, with
+ * x_act the bf16 [N][H][W][C] activation the forward pass consumed.  Where the tile kernel allows it the
+ * mask is applied in the convolution's own epilogue, saving one read and one write of dx. */
+int wap_conv2d_bwd_data_relu(const wap_conv_desc* d, const void* dy, const void* w, const void* x_act,
+                             void* dx, void* ws, size_t ws_bytes, void* stream);
+
 /* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride_h-pad_h+r, q*stride_w-pad_w+s, c].
  * dw: fp32 [K][R][S][C] (the tensor a gradient all-reduce would move, Section 3.2.3).
  * The split reduction is summed in a fixed order: results are bitwise reproducible. */

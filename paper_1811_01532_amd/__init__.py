@@ -134,6 +134,11 @@ def wap_conv2d_bwd_data(desc, dy, w, dx, ws=None, stream=None):
                                      ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
 
 
+def wap_conv2d_bwd_data_relu(desc, dy, w, x_act, dx, ws=None, stream=None):
+    _check(lib().wap_conv2d_bwd_data_relu(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(x_act), _ptr(dx), _ptr(ws),
+                                          ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
+
+
 def wap_conv2d_bwd_weight(desc, x, dy, dw, ws=None, stream=None):
     _check(lib().wap_conv2d_bwd_weight(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(dw), _ptr(ws),
                                        ctypes.c_size_t(_nbytes(ws)), _stream(stream)))

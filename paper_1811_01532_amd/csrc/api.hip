@@ -192,6 +192,20 @@ int wap_conv2d_bwd_data(const wap_conv_desc* d, const void* dy, const void* w, v
                            (hipStream_t)stream);
 }
 
+int wap_conv2d_bwd_data_relu(const wap_conv_desc* d, const void* dy, const void* w, const void* x_act, void* dx,
+                             void* ws, size_t ws_bytes, void* stream) {
+    WAP_TRY(validate_conv(d));
+    WAP_TRY(check_ptr(dy, "dy"));
+    WAP_TRY(check_ptr(w, "w"));
+    WAP_TRY(check_ptr(x_act, "x_act"));
+    WAP_TRY(check_ptr(dx, "dx"));
+    GemmGeom g = geom_conv_dgrad(*d);
+    GemmPlan p = plan_fwd_like(g, true);
+    WAP_TRY(check_ws(p.ws_bytes, ws, ws_bytes));
+    return launch_fwd_like(g, true, p, (const bf16_t*)dy, (const bf16_t*)w, nullptr, false, (bf16_t*)dx, ws,
+                           (hipStream_t)stream, nullptr, (const bf16_t*)x_act);
+}
+
 int wap_conv2d_bwd_weight(const wap_conv_desc* d, const void* x, const void* dy, float* dw, void* ws,
                           size_t ws_bytes, void* stream) {
     WAP_TRY(validate_conv(d));

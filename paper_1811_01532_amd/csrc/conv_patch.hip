@@ -30,6 +30,7 @@ struct PArgs {
     const bf16_t* A;
     const bf16_t* Wp;  // packed weights
     const float* bias;
+    const bf16_t* mask;  // optional: out = mask > 0 ? out : 0
     void* out;
     GemmGeom g;
     int tiles_m, tiles_n;
@@ -48,6 +49,17 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
 __device__ __forceinline__ unsigned short f2bf(float f) {
     __bf16 b = (__bf16)f;
     return __builtin_bit_cast(unsigned short, b);
+}
+
+// keeps the bf16 lanes of v whose mask lane is > 0 (the ReLU derivative of the layer that produced the mask)
+__device__ __forceinline__ u32x4 relu_mask8(u32x4 v, u32x4 mk) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const unsigned lo = __uint_as_float(mk[k] << 16) > 0.f ? 0xffffu : 0u;
+        const unsigned hi = __uint_as_float(mk[k] & 0xffff0000u) > 0.f ? 0xffff0000u : 0u;
+        v[k] &= (lo | hi);
+    }
+    return v;
 }
 
 // PV: 16-byte patch vectors per thread (patch rows <= PV * 32); FN: 32-channel blocks per wavefront
@@ -256,6 +268,7 @@ __global__ __launch_bounds__(NT) void conv_patch_kernel(const PArgs a) {
                 const int n = n0 + (tid % VPR) * 8;
                 if (m <= m_last && n < g.Ncols) {
                     u32x4 vv = *reinterpret_cast<const u32x4*>(smem + row * OPITCH + (tid % VPR) * 16);
+                    if (a.mask) vv = relu_mask8(vv, *reinterpret_cast<const u32x4*>(a.mask + (size_t)m * g.Ncols + n));
                     *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(a.out) + (size_t)m * g.Ncols + n) = vv;
                 }
             }
@@ -341,7 +354,7 @@ int launch_patch_t(const PArgs& pa, hipStream_t st) {
 int patch_supported(const GemmGeom& g) {
     if ((g.IC % BK) != 0 || g.div_h != 1 || g.div_w != 1 || g.mul_h != 1 || g.mul_w != 1) return 0;
     if (g.R * g.S < 2) return 0;                       // nothing to reuse for 1x1
-    if (g.Ncols < 128 || g.M < BM * 64) return 0;      // thin or tiny shapes stay on the other kernels
+    if (g.Ncols < 128 || g.M < BM * 32) return 0;      // thin or tiny shapes stay on the other kernels
     long a_elems = (long)(g.M / ((long)g.OH * g.OW)) * g.IH * g.IW * g.IC;
     if (a_elems * 2 >= (1L << 31)) return 0;
     int len = max_patch_len(g);
@@ -350,8 +363,10 @@ int patch_supported(const GemmGeom& g) {
 }
 
 int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                 hipStream_t st) {
+                 hipStream_t st, const bf16_t* mask) {
     PArgs pa;
+    if (mask && (g.Ncols & 7)) return set_error(WAP_EINVAL, "internal: fused mask needs 16-byte output rows");
+    pa.mask = mask;
     pa.A = A;
     pa.Wp = reinterpret_cast<const bf16_t*>(Wp);
     pa.bias = bias;
@@ -369,8 +384,9 @@ int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float
     pa.a_bytes = (unsigned)((size_t)(g.M / (g.OH * g.OW)) * g.IH * g.IW * g.IC * 2);
     pa.w_bytes = (unsigned)wreg_wt_bytes(g);
     pa.tiles_m = (g.M + BM - 1) / BM;
-    const bool wide = g.Ncols > 128;
-    pa.tiles_n = wide ? (g.Ncols + 255) / 256 : 1;
+    // 256-channel tiles unless they would leave a third of the CUs without a work-group
+    const bool wide = g.Ncols > 128 && (long)pa.tiles_m * ((g.Ncols + 255) / 256) >= kNumCU * 2 / 3;
+    pa.tiles_n = wide ? (g.Ncols + 255) / 256 : (g.Ncols + 127) / 128;
     if (pa.patch_cap == 384) return wide ? launch_patch_t<12, 2>(pa, st) : launch_patch_t<12, 1>(pa, st);
     return wide ? launch_patch_t<18, 2>(pa, st) : launch_patch_t<18, 1>(pa, st);
 }

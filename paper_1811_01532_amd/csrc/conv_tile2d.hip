@@ -30,6 +30,7 @@ struct TArgs {
     const bf16_t* A;
     const bf16_t* Wp;  // packed weights
     const float* bias;
+    const bf16_t* mask;  // optional: out = mask > 0 ? out : 0
     bf16_t* out;
     GemmGeom g;
     int tiles_x, tiles_y, tiles_img, tiles_m, tiles_n;
@@ -47,6 +48,17 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
 __device__ __forceinline__ unsigned short f2bf(float f) {
     __bf16 b = (__bf16)f;
     return __builtin_bit_cast(unsigned short, b);
+}
+
+// keeps the bf16 lanes of v whose mask lane is > 0 (the ReLU derivative of the layer that produced the mask)
+__device__ __forceinline__ u32x4 relu_mask8(u32x4 v, u32x4 mk) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const unsigned lo = __uint_as_float(mk[k] << 16) > 0.f ? 0xffffu : 0u;
+        const unsigned hi = __uint_as_float(mk[k] & 0xffff0000u) > 0.f ? 0xffff0000u : 0u;
+        v[k] &= (lo | hi);
+    }
+    return v;
 }
 
 // FN: 32-channel blocks per wavefront (tile = 64 * FN output channels); TW: tile width in pixels (32 or 16)
@@ -210,7 +222,9 @@ __global__ __launch_bounds__(NT, (FN == 1 ? 3 : 2)) void conv_tile2d_kernel(cons
             const int idx = (FN == 1) ? row : ((row >> 6) * (BM / 2) + half * (BM / 4) + (row & 63));
             const int m = (img * g.OH + oh0 + idx / TW) * g.OW + ow0 + idx % TW;
             u32x4 vv = *reinterpret_cast<const u32x4*>(smem + row * OPITCH + (tid % VPR) * 16);
-            *reinterpret_cast<u32x4*>(a.out + (size_t)m * g.Ncols + n0 + (tid % VPR) * 8) = vv;
+            const size_t o = (size_t)m * g.Ncols + n0 + (tid % VPR) * 8;
+            if (a.mask) vv = relu_mask8(vv, *reinterpret_cast<const u32x4*>(a.mask + o));
+            *reinterpret_cast<u32x4*>(a.out + o) = vv;
         }
     }
 }
@@ -255,8 +269,9 @@ int tile2d_supported(const GemmGeom& g) {
 }
 
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                  hipStream_t st) {
+                  hipStream_t st, const bf16_t* mask) {
     TArgs ta;
+    ta.mask = mask;
     const int fn = tile2d_supported(g);
     if (!fn) return set_error(WAP_EINVAL, "internal: 2-D tile kernel not applicable");
     ta.A = A;

@@ -453,7 +453,13 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
 
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
-                    hipStream_t st, hipEvent_t ev_mid) {
+                    hipStream_t st, hipEvent_t ev_mid, const bf16_t* relu_mask) {
+    if (relu_mask && !fwd_like_fuses_mask(g, plan)) {
+        // no fused epilogue for this tile configuration: plain product, then the element-wise mask
+        int rc = launch_fwd_like(g, b_tr, plan, A, Bw, bias, relu, out, ws, st, ev_mid, nullptr);
+        if (rc != WAP_OK) return rc;
+        return launch_relu_bwd(out, relu_mask, out, (size_t)g.M * g.Ncols, st);
+    }
     if (plan.cfg == 8) return launch_conv_c3_fwd(g, A, Bw, bias, relu, out, st);
     KArgs ka;
     ka.A = A;
@@ -472,8 +478,8 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
     if (plan.cfg == 6 || plan.cfg == 7) {
         int rc0 = launch_pack_weights(g, b_tr, Bw, ws, st);
         if (rc0 != WAP_OK) return rc0;
-        return plan.cfg == 6 ? launch_patch(g, A, ws, bias, relu, out, st)
-                             : launch_tile2d(g, A, ws, bias, relu, out, st);
+        return plan.cfg == 6 ? launch_patch(g, A, ws, bias, relu, out, st, relu_mask)
+                             : launch_tile2d(g, A, ws, bias, relu, out, st, relu_mask);
     }
     if (plan.cfg == 5) {
         // the (small) weight tensor is first repacked into MFMA fragment order (taps flipped and
@@ -531,6 +537,9 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
 }  // namespace wap
 
 namespace wap {
+bool fwd_like_fuses_mask(const GemmGeom& g, const GemmPlan& plan) {
+    return (plan.cfg == 6 || plan.cfg == 7) && (g.Ncols % 8) == 0;
+}
 // Label of the kernel instantiation a plan launches (matches the demangled kernel name).
 const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan) {
     if (plan.cfg == 5) return "conv_wreg_kernel";

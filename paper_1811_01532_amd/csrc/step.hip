@@ -31,6 +31,7 @@ struct Op {
     WgradGeom wg;
     WgradPlan wp;
     bool b_tr = false, relu = false;
+    bool has_mask = false;  // data gradient fused with the ReLU derivative of the layer below (mask tensor at t3)
     size_t t0 = 0, t1 = 0, t2 = 0, t3 = 0, t4 = 0;  // arena offsets, meaning per kind
     int N = 0, H = 0, W = 0, C = 0, win = 0, st = 0;  // pooling / softmax shapes
     size_t n = 0;
@@ -100,7 +101,8 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
         case OP_CONV_DGRAD:
         case OP_FC_DX:
             return launch_fwd_like(op.gg, op.b_tr, op.gp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
-                                   nullptr, op.relu, (bf16_t*)(base + op.t2), ws, st, ev_mid);
+                                   nullptr, op.relu, (bf16_t*)(base + op.t2), ws, st, ev_mid,
+                                   op.has_mask ? (const bf16_t*)(base + op.t3) : nullptr);
         case OP_CONV_WGRAD:
         case OP_FC_DW:
             return launch_wgrad(op.wg, op.wp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
@@ -327,6 +329,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
     }
 
     // ---- backward: conv stack ----
+    bool relu_done = false;  // the gradient in g_cur already carries this layer's ReLU derivative
     for (int i = nconv - 1; i >= 0; --i) {
         std::string nm = lname(i);
         const wap_conv_desc& d = cds[i];
@@ -342,7 +345,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             op.bytes = 2.0 * conv_y_elems[i] + 5.0 * pool_y_elems[i];
             p->ops.push_back(op);
             g_cur = op.t3;
-        } else {
+        } else if (!relu_done) {
             Op op;
             op.kind = OP_RELU_BWD; op.name = nm + ".relu_bwd";
             op.n = conv_y_elems[i];
@@ -361,6 +364,17 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             size_t g_in = new_grad(in_name, (size_t)B * d.H * d.W * d.C);
             push_fwd_like(OP_CONV_DGRAD, nm + ".dgrad", geom_conv_dgrad(d), true, false, g_cur, p->wb_off + poff[i] * 2,
                           g_in);
+            // When the layer below feeds this one directly (no pool in between) its ReLU derivative is applied in
+            // this data gradient's epilogue; the kept-gradients layout keeps the two steps apart for inspection.
+            relu_done = false;
+            Op& dg = p->ops.back();
+            if (!keep && !convs[i - 1].pool_win && fwd_like_fuses_mask(dg.gg, dg.gp)) {
+                dg.has_mask = true;
+                dg.t3 = conv_y[i - 1];
+                dg.name = nm + ".dgrad+relu_bwd";
+                dg.bytes += 2.0 * conv_y_elems[i - 1];
+                relu_done = true;
+            }
             g_cur = g_in;
         }
     }

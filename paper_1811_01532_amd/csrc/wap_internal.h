@@ -71,7 +71,9 @@ struct GemmPlan {
 GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr);
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
-                    hipStream_t st, hipEvent_t ev_mid = nullptr);  // ev_mid: recorded between kernel and split epilogue
+                    hipStream_t st, hipEvent_t ev_mid = nullptr,  // ev_mid: recorded between kernel and split epilogue
+                    const bf16_t* relu_mask = nullptr);  // out = relu_mask > 0 ? out : 0 (same shape as out)
+bool fwd_like_fuses_mask(const GemmGeom& g, const GemmPlan& plan);  // mask applied in the kernel's own epilogue?
 
 // Weight-gradient product: dw[k][(r,s,c)] = sum over pixels of dy[pix][k] * x[pix @ (r,s)][c].
 struct WgradGeom {
@@ -109,12 +111,12 @@ int launch_wreg(const GemmGeom& g, int nsplit, const bf16_t* A, const bf16_t* Bw
 // stride-1 convolution with the input patch resident in LDS (conv_patch.hip)
 int patch_supported(const GemmGeom& g);
 int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                 hipStream_t st);
+                 hipStream_t st, const bf16_t* mask = nullptr);
 
 // stride-1 convolution on 8 x 32-pixel 2-D tiles for 64 / 128 output channels (conv_tile2d.hip)
 int tile2d_supported(const GemmGeom& g);
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                  hipStream_t st);
+                  hipStream_t st, const bf16_t* mask = nullptr);
 
 const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan);
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan);

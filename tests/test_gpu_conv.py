@@ -102,6 +102,17 @@ def test_conv_three_passes_match_oracle(orc, name, shape, force):
         refdx = orc.conv2d_bwd_data(g64, w64, (N, H, W, C), stride, pad)
         e = gu.rel_err(gu.host_f64(dx), refdx)
         assert e <= gu.TOL and e <= gu.TOL_BF16_OUT, f"dgrad rel err {e}"
+        # ---- data gradient fused with the ReLU derivative of the producer of x (mask = relu(x) > 0);
+        # bitwise the same as masking the plain data gradient afterwards ----
+        xact = torch.relu(xd)
+        dxm = torch.full((N, H, W, C), float("nan"), dtype=torch.bfloat16, device="cuda")
+        wap.wap_conv2d_bwd_data_relu(d, gd, wd, xact, dxm, ws)
+        torch.cuda.synchronize()
+        refm = orc.relu_bwd(refdx, np.maximum(x64, 0.0))
+        e = gu.rel_err(gu.host_f64(dxm), refm)
+        assert e <= gu.TOL and e <= gu.TOL_BF16_OUT, f"dgrad+relu rel err {e}"
+        keep = (xact > 0)
+        assert torch.equal(torch.where(keep, dx, torch.zeros_like(dx)), dxm)
         # ---- weight gradient (fp32 out) ----
         dw = torch.full((K, R, S, C), float("nan"), dtype=torch.float32, device="cuda")
         ws = gu.workspace(wap.wap_conv2d_workspace_bytes(d, wap.WAP_PASS_BWD_WEIGHT))
