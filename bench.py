@@ -235,7 +235,7 @@ def main():
         k["flops"] += fl
         k["bytes"] += by
         if ue > 0:   # split-reduction epilogue kernel of this operation, timed on its own
-            ek = "reduce_f32_kernel" if kernel.startswith("wgrad") else "reduce_bf16_kernel"
+            ek = "reduce_f32*_kernel" if kernel.startswith("wgrad") else "reduce_bf16_kernel"
             k2 = kern.setdefault(ek, {"kernel": ek, "launches": 0, "us": 0.0, "flops": 0.0, "bytes": 0.0})
             k2["launches"] += 1
             k2["us"] += ue

@@ -362,6 +362,21 @@ int patch_supported(const GemmGeom& g) {
     return len <= 384 ? 384 : 560;
 }
 
+namespace {
+// 256-channel tiles unless they would leave a third of the CUs without a work-group
+bool patch_wide(const GemmGeom& g) {
+    const long tiles_m = (g.M + BM - 1) / BM;
+    return g.Ncols > 128 && tiles_m * ((g.Ncols + 255) / 256) >= kNumCU * 2 / 3;
+}
+}  // namespace
+
+const char* patch_kernel_name(const GemmGeom& g) {
+    const int cap = patch_supported(g);
+    const bool wide = patch_wide(g);
+    if (cap == 384) return wide ? "conv_patch_kernel<12,2>" : "conv_patch_kernel<12,1>";
+    return wide ? "conv_patch_kernel<18,2>" : "conv_patch_kernel<18,1>";
+}
+
 int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
                  hipStream_t st, const bf16_t* mask) {
     PArgs pa;
@@ -384,8 +399,7 @@ int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float
     pa.a_bytes = (unsigned)((size_t)(g.M / (g.OH * g.OW)) * g.IH * g.IW * g.IC * 2);
     pa.w_bytes = (unsigned)wreg_wt_bytes(g);
     pa.tiles_m = (g.M + BM - 1) / BM;
-    // 256-channel tiles unless they would leave a third of the CUs without a work-group
-    const bool wide = g.Ncols > 128 && (long)pa.tiles_m * ((g.Ncols + 255) / 256) >= kNumCU * 2 / 3;
+    const bool wide = patch_wide(g);
     pa.tiles_n = wide ? (g.Ncols + 255) / 256 : (g.Ncols + 127) / 128;
     if (pa.patch_cap == 384) return wide ? launch_patch_t<12, 2>(pa, st) : launch_patch_t<12, 1>(pa, st);
     return wide ? launch_patch_t<18, 2>(pa, st) : launch_patch_t<18, 1>(pa, st);

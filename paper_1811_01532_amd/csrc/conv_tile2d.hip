@@ -268,6 +268,13 @@ int tile2d_supported(const GemmGeom& g) {
     return g.Ncols == 64 ? 1 : 2;
 }
 
+const char* tile2d_kernel_name(const GemmGeom& g) {
+    static const char* names[2][3] = {{"conv_tile2d_kernel<1,32>", "conv_tile2d_kernel<1,16>", "conv_tile2d_kernel<1,8>"},
+                                      {"conv_tile2d_kernel<2,32>", "conv_tile2d_kernel<2,16>", "conv_tile2d_kernel<2,8>"}};
+    const int fn = tile2d_supported(g), tw = tile_width(g);
+    return names[fn == 2 ? 1 : 0][tw == 32 ? 0 : tw == 16 ? 1 : 2];
+}
+
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
                   hipStream_t st, const bf16_t* mask) {
     TArgs ta;

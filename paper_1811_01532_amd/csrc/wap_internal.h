@@ -91,6 +91,7 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
 // stride-1 3x3 weight gradient with the input patch resident in LDS (wgrad_patch.hip)
 bool wgrad_patch_supported(const WgradGeom& g);
 int wgrad_patch_nsplit(const WgradGeom& g);
+const char* wgrad_patch_kernel_name(const WgradGeom& g);
 int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* out, hipStream_t st);
 
 // 3-input-channel 3x3 stride-1 first layer (conv_c3.hip)
@@ -110,11 +111,13 @@ int launch_wreg(const GemmGeom& g, int nsplit, const bf16_t* A, const bf16_t* Bw
 
 // stride-1 convolution with the input patch resident in LDS (conv_patch.hip)
 int patch_supported(const GemmGeom& g);
+const char* patch_kernel_name(const GemmGeom& g);
 int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
                  hipStream_t st, const bf16_t* mask = nullptr);
 
 // stride-1 convolution on 8 x 32-pixel 2-D tiles for 64 / 128 output channels (conv_tile2d.hip)
 int tile2d_supported(const GemmGeom& g);
+const char* tile2d_kernel_name(const GemmGeom& g);
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
                   hipStream_t st, const bf16_t* mask = nullptr);
 

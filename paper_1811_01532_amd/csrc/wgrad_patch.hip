@@ -254,6 +254,10 @@ bool wgrad_patch_supported(const WgradGeom& g) {
     return ts.TH * ts.TWr >= 64;  // tiny tiles: the generic kernel is no worse
 }
 
+const char* wgrad_patch_kernel_name(const WgradGeom& g) {
+    return fd_for(g) == 2 ? "wgrad_patch_kernel<2>" : "wgrad_patch_kernel<1>";
+}
+
 int wgrad_patch_nsplit(const WgradGeom& g) {
     TileShape ts;
     if (!choose_tile(g, &ts)) return 1;
