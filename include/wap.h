@@ -211,9 +211,19 @@ int wap_step_op_info(const wap_step_plan* p, int32_t index, const char** name, c
 /* Runs `steps` steps back to back with a HIP event pair around every operation (events are created
  * on first use and cached in the plan); fills us_out[num_ops] with the mean duration in microseconds
  * of each operation's main kernel and us_epilogue_out[num_ops] with that of its split-reduction
- * epilogue kernel (0 where the operation has none).  Synchronises the stream once, at the end. */
+ * epilogue kernel (0 where the operation has none).  The weight-repacking kernel that precedes some
+ * convolution kernels is outside both (see wap_step_time_masked).  Synchronises the stream once, at
+ * the end. */
 int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
                   float* us_out, float* us_epilogue_out);
+/* The same with events only around the operations whose op_mask[index] is non-zero (host array of
+ * num_ops bytes, NULL = all): the other operations run unbracketed and report 0, so that a timed
+ * region can carry the events of one kernel without the launch gaps the full instrumentation adds
+ * (two event records per operation, about 0.5 ms per VGG-16 step). */
+int wap_step_time_masked(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
+                         const uint8_t* op_mask, float* us_out, float* us_epilogue_out, float* us_prologue_out);
+/* us_prologue_out (host, num_ops floats, may be NULL): mean duration of the weight-repacking kernel an
+ * operation launches before its main kernel (0 where it has none). */
 
 #ifdef __cplusplus
 }

@@ -254,11 +254,21 @@ class StepPlan:
             out.append((name.value.decode(), kern.value.decode(), fl.value, by.value))
         return out
 
-    def time(self, arena, steps=1, stream=None):
-        """`steps` steps with events around every operation: (main-kernel us, epilogue-kernel us) lists."""
+    def time(self, arena, steps=1, stream=None, op_mask=None, with_prologue=False):
+        """`steps` steps with events around every operation (or only those whose op_mask entry is true):
+        (main-kernel us, epilogue-kernel us) lists, plus the weight-repacking-kernel us list on request."""
         n = self.num_ops()
         us = (ctypes.c_float * n)()
         epi = (ctypes.c_float * n)()
-        _check(lib().wap_step_time(self._p, _ptr(arena), ctypes.c_size_t(_nbytes(arena)), _stream(stream),
-                                   int(steps), us, epi))
+        pro = (ctypes.c_float * n)()
+        mask = None
+        if op_mask is not None:
+            if len(op_mask) != n:
+                raise ValueError("op_mask needs one entry per operation")
+            mask = (ctypes.c_uint8 * n)(*[1 if m else 0 for m in op_mask])
+        _check(lib().wap_step_time_masked(self._p, _ptr(arena), ctypes.c_size_t(_nbytes(arena)), _stream(stream),
+                                          int(steps), mask, us, epi, pro))
+        if with_prologue:
+            return ([float(us[i]) for i in range(n)], [float(epi[i]) for i in range(n)],
+                    [float(pro[i]) for i in range(n)])
         return [float(us[i]) for i in range(n)], [float(epi[i]) for i in range(n)]

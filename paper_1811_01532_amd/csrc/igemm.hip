@@ -453,10 +453,10 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
 
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
-                    hipStream_t st, hipEvent_t ev_mid, const bf16_t* relu_mask) {
+                    hipStream_t st, hipEvent_t ev_mid, const bf16_t* relu_mask, hipEvent_t ev_packed) {
     if (relu_mask && !fwd_like_fuses_mask(g, plan)) {
         // no fused epilogue for this tile configuration: plain product, then the element-wise mask
-        int rc = launch_fwd_like(g, b_tr, plan, A, Bw, bias, relu, out, ws, st, ev_mid, nullptr);
+        int rc = launch_fwd_like(g, b_tr, plan, A, Bw, bias, relu, out, ws, st, ev_mid, nullptr, ev_packed);
         if (rc != WAP_OK) return rc;
         return launch_relu_bwd(out, relu_mask, out, (size_t)g.M * g.Ncols, st);
     }
@@ -478,6 +478,7 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
     if (plan.cfg == 6 || plan.cfg == 7) {
         int rc0 = launch_pack_weights(g, b_tr, Bw, ws, st);
         if (rc0 != WAP_OK) return rc0;
+        if (ev_packed) (void)hipEventRecord(ev_packed, st);
         return plan.cfg == 6 ? launch_patch(g, A, ws, bias, relu, out, st, relu_mask)
                              : launch_tile2d(g, A, ws, bias, relu, out, st, relu_mask);
     }
@@ -486,6 +487,7 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
         // transposed for the data gradient); the partial tiles, if any, follow it in the workspace
         int rc0 = launch_pack_weights(g, b_tr, Bw, ws, st);
         if (rc0 != WAP_OK) return rc0;
+        if (ev_packed) (void)hipEventRecord(ev_packed, st);
         void* part = reinterpret_cast<unsigned char*>(ws) + wreg_wt_bytes(g);
         int rc5 = launch_wreg(g, plan.nsplit, A, reinterpret_cast<const bf16_t*>(ws), bias, relu,
                               ka.partial ? part : (void*)out, ka.partial != 0, st);
@@ -537,6 +539,7 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
 }  // namespace wap
 
 namespace wap {
+bool fwd_like_packs_weights(const GemmPlan& plan) { return plan.cfg == 5 || plan.cfg == 6 || plan.cfg == 7; }
 bool fwd_like_fuses_mask(const GemmGeom& g, const GemmPlan& plan) {
     return (plan.cfg == 6 || plan.cfg == 7) && (g.Ncols % 8) == 0;
 }

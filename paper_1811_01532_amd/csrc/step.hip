@@ -93,7 +93,8 @@ struct wap_step_plan {
 
 namespace {
 
-int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_t st, hipEvent_t ev_mid = nullptr) {
+int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_t st, hipEvent_t ev_mid = nullptr,
+           hipEvent_t ev_packed = nullptr) {
     void* ws = base + p->ws_off;
     switch (op.kind) {
         case OP_CONV_FWD:
@@ -102,7 +103,7 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
         case OP_FC_DX:
             return launch_fwd_like(op.gg, op.b_tr, op.gp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
                                    nullptr, op.relu, (bf16_t*)(base + op.t2), ws, st, ev_mid,
-                                   op.has_mask ? (const bf16_t*)(base + op.t3) : nullptr);
+                                   op.has_mask ? (const bf16_t*)(base + op.t3) : nullptr, ev_packed);
         case OP_CONV_WGRAD:
         case OP_FC_DW:
             return launch_wgrad(op.wg, op.wp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
@@ -453,13 +454,18 @@ int wap_step_op_info(const wap_step_plan* p, int32_t index, const char** name, c
 
 int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
                   float* us_out, float* us_epilogue_out) {
+    return wap_step_time_masked(p, arena, arena_bytes, stream, steps, nullptr, us_out, us_epilogue_out, nullptr);
+}
+
+int wap_step_time_masked(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
+                         const uint8_t* op_mask, float* us_out, float* us_epilogue_out, float* us_prologue_out) {
     int rc = check_arena(p, arena, arena_bytes);
     if (rc != WAP_OK) return rc;
     if (!us_out || !us_epilogue_out || steps < 1) return set_error(WAP_EINVAL, "step: bad argument");
     unsigned char* base = (unsigned char*)arena;
     hipStream_t st = (hipStream_t)stream;
     const size_t n = p->ops.size();
-    const size_t need = 3 * n * (size_t)steps;
+    const size_t need = 4 * n * (size_t)steps;
     while (p->events.size() < need) {
         hipEvent_t e;
         if (hipEventCreate(&e) != hipSuccess) return set_error(WAP_EHIP, "hipEventCreate failed");
@@ -472,11 +478,22 @@ int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void*
             default: return false;
         }
     };
+    auto has_prologue = [&](const Op& op) {
+        switch (op.kind) {
+            case OP_CONV_FWD: case OP_FC_FWD: case OP_CONV_DGRAD: case OP_FC_DX: return fwd_like_packs_weights(op.gp);
+            default: return false;
+        }
+    };
     for (int s = 0; s < steps && rc == WAP_OK; ++s)
         for (size_t i = 0; i < n && rc == WAP_OK; ++i) {
-            hipEvent_t* ev = &p->events[3 * ((size_t)s * n + i)];
+            hipEvent_t* ev = &p->events[4 * ((size_t)s * n + i)];
+            if (op_mask && !op_mask[i]) {
+                rc = run_op(p, p->ops[i], base, st, nullptr);
+                continue;
+            }
             (void)hipEventRecord(ev[0], st);
-            rc = run_op(p, p->ops[i], base, st, has_epilogue(p->ops[i]) ? ev[2] : nullptr);
+            rc = run_op(p, p->ops[i], base, st, has_epilogue(p->ops[i]) ? ev[2] : nullptr,
+                        has_prologue(p->ops[i]) ? ev[3] : nullptr);
             (void)hipEventRecord(ev[1], st);
         }
     hipError_t e = hipStreamSynchronize(st);
@@ -485,19 +502,34 @@ int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void*
     for (size_t i = 0; i < n; ++i) {
         double sum = 0, sum_epi = 0;
         const bool epi = has_epilogue(p->ops[i]);
+        if (us_prologue_out) us_prologue_out[i] = 0.f;
+        if (op_mask && !op_mask[i]) {
+            us_out[i] = 0.f;
+            us_epilogue_out[i] = 0.f;
+            continue;
+        }
+        const bool pro = has_prologue(p->ops[i]);
+        double sum_pro = 0;
         for (int s = 0; s < steps; ++s) {
             float ms = 0.f;
-            hipEvent_t* ev = &p->events[3 * ((size_t)s * n + i)];
+            hipEvent_t* ev = &p->events[4 * ((size_t)s * n + i)];
+            hipEvent_t first = ev[0];
+            if (pro) {
+                (void)hipEventElapsedTime(&ms, ev[0], ev[3]);
+                sum_pro += ms;
+                first = ev[3];
+            }
             if (epi) {
-                (void)hipEventElapsedTime(&ms, ev[0], ev[2]);
+                (void)hipEventElapsedTime(&ms, first, ev[2]);
                 sum += ms;
                 (void)hipEventElapsedTime(&ms, ev[2], ev[1]);
                 sum_epi += ms;
             } else {
-                (void)hipEventElapsedTime(&ms, ev[0], ev[1]);
+                (void)hipEventElapsedTime(&ms, first, ev[1]);
                 sum += ms;
             }
         }
+        if (us_prologue_out) us_prologue_out[i] = (float)(sum_pro * 1000.0 / steps);
         us_out[i] = (float)(sum * 1000.0 / steps);
         us_epilogue_out[i] = (float)(sum_epi * 1000.0 / steps);
     }

@@ -72,7 +72,9 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr);
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
                     hipStream_t st, hipEvent_t ev_mid = nullptr,  // ev_mid: recorded between kernel and split epilogue
-                    const bf16_t* relu_mask = nullptr);  // out = relu_mask > 0 ? out : 0 (same shape as out)
+                    const bf16_t* relu_mask = nullptr,   // out = relu_mask > 0 ? out : 0 (same shape as out)
+                    hipEvent_t ev_packed = nullptr);     // recorded after the weight repacking, if the plan has one
+bool fwd_like_packs_weights(const GemmPlan& plan);
 bool fwd_like_fuses_mask(const GemmGeom& g, const GemmPlan& plan);  // mask applied in the kernel's own epilogue?
 
 // Weight-gradient product: dw[k][(r,s,c)] = sum over pixels of dy[pix][k] * x[pix @ (r,s)][c].
