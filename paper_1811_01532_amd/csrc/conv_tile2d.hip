@@ -21,10 +21,10 @@ namespace wap {
 
 namespace {
 
-constexpr int BK = 64, BM = 256, NT = 256, FM = 4;
+constexpr int BK = 64, NT = 256;
 constexpr int PITCH = (BK + 8) * 2;  // 144 bytes per padded pixel
 constexpr int MAX_PATCH = 352;       // padded pixels (>= (tile h + R - 1) * (tile w + S - 1)); also the staging area
-constexpr int PV = (MAX_PATCH * 8 + NT - 1) / NT;  // 16-byte patch vectors per thread
+constexpr int MAX_PATCH_FLAT = 384;  // the same for flat (raster-order) tiles, which may straddle rows and images
 
 struct TArgs {
     const bf16_t* A;
@@ -34,10 +34,12 @@ struct TArgs {
     bf16_t* out;
     GemmGeom g;
     int tiles_x, tiles_y, tiles_img, tiles_m, tiles_n;
-    int PWp, patch_len;  // padded tile width, padded pixels per patch
+    int PWp, patch_len;  // padded tile (flat tiles: image) width, padded pixels per patch (2-D tiles)
+    int PH;              // flat tiles: padded image height
     int relu;
     unsigned a_bytes, w_bytes;
     FastDiv dTimg, dTx, dPWp;
+    FastDiv dOHW, dOW, dPHW;  // flat tiles
 };
 
 __device__ __forceinline__ int xcd_remap(int bid, int total) {
@@ -61,15 +63,25 @@ __device__ __forceinline__ u32x4 relu_mask8(u32x4 v, u32x4 mk) {
     return v;
 }
 
-// FN: 32-channel blocks per wavefront (tile = 64 * FN output channels); TW: tile width in pixels (32 or 16)
-template <int FN, int TW>
-__global__ __launch_bounds__(NT, (FN == 1 ? 3 : 2)) void conv_tile2d_kernel(const TArgs a) {
-    constexpr int TH = BM / TW;
+// FN: 32-channel blocks per wavefront; TW: tile width in pixels; FM: 32-pixel fragments per wavefront;
+// PG: wavefronts along the pixels (4 / PG along the channels).  Tile = 32*FM*PG pixels x 32*FN*(4/PG) channels.
+// TW = 0: flat tiles, 32*FM*PG consecutive output pixels in raster order (they may straddle rows and images;
+// the patch is then a run of the zero-padded image in raster order, as in conv_patch.hip).
+template <int FN, int TW, int FM, int PG>
+__global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel(const TArgs a) {
+    constexpr bool FLAT = (TW == 0);
+    constexpr int BM = 32 * FM * PG;
+    constexpr int CG = 4 / PG;
+    constexpr int TWD = FLAT ? 1 : TW;  // divisor that is never zero
+    constexpr int TH = BM / TWD;
+    static_assert(FLAT || TH * TW == BM, "tile width must divide the tile");
+    constexpr int PATCH_ROWS = FLAT ? MAX_PATCH_FLAT : MAX_PATCH;
+    constexpr int PV = (PATCH_ROWS * 8 + NT - 1) / NT;  // 16-byte patch vectors per thread
     extern __shared__ __align__(16) unsigned char smem[];
     const GemmGeom& g = a.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int pg = wave & 1, cg = wave >> 1;  // pixel half, channel half
-    constexpr int BN = 64 * FN;
+    const int pg = wave % PG, cg = wave / PG;  // pixel group, channel group
+    constexpr int BN = 32 * FN * CG;
 
     int logical = xcd_remap(blockIdx.x, a.tiles_m * a.tiles_n);
     const int tn = logical % a.tiles_n;
@@ -79,6 +91,18 @@ __global__ __launch_bounds__(NT, (FN == 1 ? 3 : 2)) void conv_tile2d_kernel(cons
     const int tyi = (int)fdiv((uint32_t)trem, a.dTx);
     const int oh0 = tyi * TH, ow0 = (trem - tyi * a.tiles_x) * TW;
     const int n0 = tn * BN;
+    // flat tiles: padded-flat index ((n * PH + oh) * PW + ow) of output pixel m at tap (0,0)
+    const int OHW = g.OH * g.OW, PHW = a.PH * a.PWp;
+    auto pflat = [&](int m) {
+        int n = (int)fdiv((uint32_t)m, a.dOHW);
+        int rem = m - n * OHW;
+        int oh = (int)fdiv((uint32_t)rem, a.dOW);
+        return n * PHW + oh * a.PWp + (rem - oh * g.OW);
+    };
+    const int m0 = tm * BM;
+    const int m_last = (m0 + BM <= g.M ? m0 + BM : g.M) - 1;
+    const int p_lo = FLAT ? pflat(m0) : 0;
+    const int patch_len = FLAT ? pflat(m_last) + (g.R - 1) * a.PWp + (g.S - 1) + 1 - p_lo : a.patch_len;
     const int RS = g.R * g.S;
     const int ncs = g.IC / BK;
 
@@ -95,12 +119,22 @@ __global__ __launch_bounds__(NT, (FN == 1 ? 3 : 2)) void conv_tile2d_kernel(cons
         int v = tid + i * NT;
         int q = v >> 3;
         unsigned off = OOB;
-        if (q < a.patch_len) {
-            int py = (int)fdiv((uint32_t)q, a.dPWp);
-            int px = q - py * a.PWp;
-            int ih = oh0 - g.pad_h + py, iw = ow0 - g.pad_w + px;
-            if ((unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW)
-                off = (unsigned)(((img * g.IH + ih) * g.IW + iw) * g.IC + (v & 7) * 8) * 2u;
+        if (q < patch_len) {
+            if (FLAT) {
+                int p = p_lo + q;
+                int n = (int)fdiv((uint32_t)p, a.dPHW);
+                int rem = p - n * PHW;
+                int vh = (int)fdiv((uint32_t)rem, a.dPWp);
+                int ih = vh - g.pad_h, iw = rem - vh * a.PWp - g.pad_w;
+                if (n * OHW < g.M && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW)
+                    off = (unsigned)(((n * g.IH + ih) * g.IW + iw) * g.IC + (v & 7) * 8) * 2u;
+            } else {
+                int py = (int)fdiv((uint32_t)q, a.dPWp);
+                int px = q - py * a.PWp;
+                int ih = oh0 - g.pad_h + py, iw = ow0 - g.pad_w + px;
+                if ((unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW)
+                    off = (unsigned)(((img * g.IH + ih) * g.IW + iw) * g.IC + (v & 7) * 8) * 2u;
+            }
         }
         pvoff[i] = off;
     }
@@ -110,7 +144,12 @@ __global__ __launch_bounds__(NT, (FN == 1 ? 3 : 2)) void conv_tile2d_kernel(cons
 #pragma unroll
     for (int j = 0; j < FM; ++j) {
         const int idx = (pg * FM + j) * 32 + (lane & 31);
-        frow[j] = ((idx / TW) * a.PWp + (idx % TW)) * PITCH + (lane >> 5) * 16;
+        if (FLAT) {
+            const int m = m0 + idx <= m_last ? m0 + idx : m_last;  // tile tail: computed on a valid pixel, never stored
+            frow[j] = (pflat(m) - p_lo) * PITCH + (lane >> 5) * 16;
+        } else {
+            frow[j] = ((idx / TWD) * a.PWp + (idx % TWD)) * PITCH + (lane >> 5) * 16;
+        }
     }
 
     // ---- weights: packed [channel block of 32][reduction step of 16][lane][8] ----
@@ -152,7 +191,7 @@ __global__ __launch_bounds__(NT, (FN == 1 ? 3 : 2)) void conv_tile2d_kernel(cons
 #pragma unroll
             for (int i = 0; i < PV; ++i) {
                 int v = tid + i * NT;
-                if ((v >> 3) < MAX_PATCH) *reinterpret_cast<u32x4*>(smem + (v >> 3) * PITCH + (v & 7) * 16) = rp[i];
+                if ((v >> 3) < PATCH_ROWS) *reinterpret_cast<u32x4*>(smem + (v >> 3) * PITCH + (v & 7) * 16) = rp[i];
             }
         }
         __syncthreads();
@@ -185,16 +224,19 @@ __global__ __launch_bounds__(NT, (FN == 1 ? 3 : 2)) void conv_tile2d_kernel(cons
     constexpr int OPITCH = BN * 2 + 16;  // bytes per pixel row in the staging buffer
     constexpr int VPR = BN / 8;          // 16-byte vectors per pixel row
     constexpr int RPP = NT / VPR;        // pixel rows stored per pass
-    constexpr int HROWS = (FN == 1) ? BM : BM / 2;  // pixel rows staged per pass (fits the patch area)
+    // fragments of every pixel group staged per pass: as many as fit the (dead) patch area
+    constexpr int JFIT = (PATCH_ROWS * PITCH) / (OPITCH * 32 * PG);
+    constexpr int JN = JFIT < FM ? JFIT : FM;
+    constexpr int HROWS = PG * JN * 32;
+    static_assert(JN >= 1, "staging area too small");
 #pragma unroll
-    for (int half = 0; half < BM / HROWS; ++half) {
+    for (int half = 0; half < (FM + JN - 1) / JN; ++half) {
         __syncthreads();  // previous readers of the staging area (or of the patch) are done
-        // FN == 1: all 8 tile rows at once; FN == 2: fragments 0-1 of both pixel halves, then fragments 2-3
-        constexpr int JN = (FN == 1) ? FM : FM / 2;
 #pragma unroll
         for (int jj = 0; jj < JN; ++jj) {
             const int j = half * JN + jj;
-            const int srow = ((FN == 1) ? (pg * FM + j) : (pg * JN + jj)) * 32 + (lane & 31);
+            if (j >= FM) continue;
+            const int srow = (pg * JN + jj) * 32 + (lane & 31);
 #pragma unroll
             for (int i = 0; i < FN; ++i)
 #pragma unroll
@@ -218,9 +260,12 @@ __global__ __launch_bounds__(NT, (FN == 1 ? 3 : 2)) void conv_tile2d_kernel(cons
         }
         __syncthreads();
         for (int row = tid / VPR; row < HROWS; row += RPP) {
-            // staged row -> tile pixel: FN == 1: the same; FN == 2: pixel half row / 64, its fragments 2 * half, 2 * half + 1
-            const int idx = (FN == 1) ? row : ((row >> 6) * (BM / 2) + half * (BM / 4) + (row & 63));
-            const int m = (img * g.OH + oh0 + idx / TW) * g.OW + ow0 + idx % TW;
+            // staged row -> (pixel group, fragment of this pass, pixel) -> tile pixel
+            const int j = half * JN + (row % (JN * 32)) / 32;
+            if (j >= FM) continue;
+            const int idx = ((row / (JN * 32)) * FM + j) * 32 + (row & 31);
+            const int m = FLAT ? m0 + idx : (img * g.OH + oh0 + idx / TWD) * g.OW + ow0 + idx % TWD;
+            if (FLAT && m > m_last) continue;
             u32x4 vv = *reinterpret_cast<const u32x4*>(smem + row * OPITCH + (tid % VPR) * 16);
             const size_t o = (size_t)m * g.Ncols + n0 + (tid % VPR) * 8;
             if (a.mask) vv = relu_mask8(vv, *reinterpret_cast<const u32x4*>(a.mask + o));
@@ -229,10 +274,10 @@ __global__ __launch_bounds__(NT, (FN == 1 ? 3 : 2)) void conv_tile2d_kernel(cons
     }
 }
 
-template <int FN, int TW>
+template <int FN, int TW, int FM, int PG>
 int launch_tile2d_t(const TArgs& ta, hipStream_t st) {
-    auto kfn = conv_tile2d_kernel<FN, TW>;
-    constexpr size_t smem = (size_t)MAX_PATCH * PITCH;
+    auto kfn = conv_tile2d_kernel<FN, TW, FM, PG>;
+    constexpr size_t smem = (size_t)(TW == 0 ? MAX_PATCH_FLAT : MAX_PATCH) * PITCH;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
@@ -247,13 +292,44 @@ int launch_tile2d_t(const TArgs& ta, hipStream_t st) {
 }  // namespace
 
 namespace {
-// tile width that divides the feature map (and whose patch fits), or 0
-int tile_width(const GemmGeom& g) {
-    for (int tw : {32, 16, 8}) {
-        const int th = BM / tw;
-        if ((g.OH % th) == 0 && (g.OW % tw) == 0 && (th + g.R - 1) * (tw + g.S - 1) <= MAX_PATCH) return tw;
+struct TileCfg {
+    int fn, tw, th, variant;  // variant 0: 256 pixels as 2 x 4 fragments; 1: 224 pixels (8 x 28) as 1 x 7 fragments,
+                              // 128 channels; 2: the same with flat tiles (224 consecutive pixels)
+};
+// largest flat patch (in padded pixels) any 224-pixel raster-order tile of this geometry needs
+int max_flat_patch(const GemmGeom& g) {
+    const int PH = g.OH + g.R - 1, PW = g.OW + g.S - 1;
+    const long OHW = (long)g.OH * g.OW;
+    auto pflat = [&](long m) {
+        long n = m / OHW, rem = m - n * OHW;
+        long oh = rem / g.OW, ow = rem - oh * g.OW;
+        return n * PH * PW + oh * PW + ow;
+    };
+    long worst = 0;
+    for (long m0 = 0; m0 < g.M; m0 += 224) {
+        long ml = (m0 + 224 <= g.M ? m0 + 224 : g.M) - 1;
+        long len = pflat(ml) + (long)(g.R - 1) * PW + (g.S - 1) + 1 - pflat(m0);
+        if (len > worst) worst = len;
     }
-    return 0;
+    return (int)worst;
+}
+// Tile shape for this geometry (width must divide the map, patch must fit), fn = 0 if none.
+TileCfg tile_cfg(const GemmGeom& g) {
+    TileCfg c = {0, 0, 0, 0};
+    if (g.Ncols != 64 && (g.Ncols % 128) != 0) return c;
+    for (int tw : {32, 16, 8}) {
+        const int th = 256 / tw;
+        if ((g.OH % th) == 0 && (g.OW % tw) == 0 && (th + g.R - 1) * (tw + g.S - 1) <= MAX_PATCH) {
+            c = {g.Ncols == 64 ? 1 : 2, tw, th, 0};
+            return c;
+        }
+    }
+    // maps of 28k x 8j pixels (56 x 56): 8 x 28 tiles, one 224-pixel strip per wavefront, 128-channel tiles
+    if ((g.Ncols % 128) == 0 && (g.OW % 28) == 0 && (g.OH % 8) == 0 && (8 + g.R - 1) * (28 + g.S - 1) <= MAX_PATCH)
+        c = {1, 28, 8, 1};
+    else if ((g.Ncols % 128) == 0 && g.M >= 224 * 4 && max_flat_patch(g) <= MAX_PATCH_FLAT)
+        c = {1, 0, 0, 2};
+    return c;
 }
 }  // namespace
 
@@ -261,48 +337,71 @@ int tile_width(const GemmGeom& g) {
 int tile2d_supported(const GemmGeom& g) {
     if ((g.IC % BK) != 0 || g.div_h != 1 || g.div_w != 1 || g.mul_h != 1 || g.mul_w != 1) return 0;
     if (g.R * g.S < 2) return 0;
-    if (!tile_width(g)) return 0;
-    if (g.Ncols != 64 && (g.Ncols % 128) != 0) return 0;
     long a_elems = (long)(g.M / ((long)g.OH * g.OW)) * g.IH * g.IW * g.IC;
     if (a_elems * 2 >= (1L << 31)) return 0;
-    return g.Ncols == 64 ? 1 : 2;
+    return tile_cfg(g).fn;
+}
+
+// Shapes on which this kernel measured faster than conv_patch.hip: thin outputs on 2-D tiles, and the 8 x 28
+// strip tiles (56-pixel-wide maps) at any width; flat tiles only tie with it and stay a forced option.
+bool tile2d_preferred(const GemmGeom& g) {
+    if (!tile2d_supported(g)) return false;
+    const TileCfg c = tile_cfg(g);
+    return (c.variant == 0 && g.Ncols <= 128) || c.variant == 1;
 }
 
 const char* tile2d_kernel_name(const GemmGeom& g) {
-    static const char* names[2][3] = {{"conv_tile2d_kernel<1,32>", "conv_tile2d_kernel<1,16>", "conv_tile2d_kernel<1,8>"},
-                                      {"conv_tile2d_kernel<2,32>", "conv_tile2d_kernel<2,16>", "conv_tile2d_kernel<2,8>"}};
-    const int fn = tile2d_supported(g), tw = tile_width(g);
-    return names[fn == 2 ? 1 : 0][tw == 32 ? 0 : tw == 16 ? 1 : 2];
+    const TileCfg c = tile_cfg(g);
+    if (c.variant == 1) return "conv_tile2d_kernel<1,28,7,1>";
+    if (c.variant == 2) return "conv_tile2d_kernel<1,0,7,1>";
+    static const char* names[2][3] = {
+        {"conv_tile2d_kernel<1,32,4,2>", "conv_tile2d_kernel<1,16,4,2>", "conv_tile2d_kernel<1,8,4,2>"},
+        {"conv_tile2d_kernel<2,32,4,2>", "conv_tile2d_kernel<2,16,4,2>", "conv_tile2d_kernel<2,8,4,2>"}};
+    return names[c.fn == 2 ? 1 : 0][c.tw == 32 ? 0 : c.tw == 16 ? 1 : 2];
 }
 
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
                   hipStream_t st, const bf16_t* mask) {
-    TArgs ta;
+    TArgs ta = {};
     ta.mask = mask;
-    const int fn = tile2d_supported(g);
-    if (!fn) return set_error(WAP_EINVAL, "internal: 2-D tile kernel not applicable");
+    if (!tile2d_supported(g)) return set_error(WAP_EINVAL, "internal: 2-D tile kernel not applicable");
+    const TileCfg c = tile_cfg(g);
+    const int fn = c.fn;
     ta.A = A;
     ta.Wp = reinterpret_cast<const bf16_t*>(Wp);
     ta.bias = bias;
     ta.out = out;
     ta.g = g;
-    const int TW = tile_width(g), TH = BM / TW;
-    ta.tiles_x = g.OW / TW;
-    ta.tiles_y = g.OH / TH;
-    ta.tiles_img = ta.tiles_x * ta.tiles_y;
-    ta.tiles_m = ta.tiles_img * (g.M / (g.OH * g.OW));
-    ta.tiles_n = g.Ncols / (64 * fn);
-    ta.PWp = TW + g.S - 1;
-    ta.patch_len = (TH + g.R - 1) * ta.PWp;
+    ta.tiles_n = c.variant >= 1 ? g.Ncols / 128 : g.Ncols / (64 * fn);
+    if (c.variant == 2) {
+        ta.tiles_x = ta.tiles_y = ta.tiles_img = 1;
+        ta.tiles_m = (g.M + 223) / 224;
+        ta.PH = g.OH + g.R - 1;
+        ta.PWp = g.OW + g.S - 1;
+        ta.patch_len = 0;  // per tile, computed in the kernel
+        ta.dOHW = make_fastdiv((uint32_t)(g.OH * g.OW));
+        ta.dOW = make_fastdiv((uint32_t)g.OW);
+        ta.dPHW = make_fastdiv((uint32_t)(ta.PH * ta.PWp));
+    } else {
+        ta.tiles_x = g.OW / c.tw;
+        ta.tiles_y = g.OH / c.th;
+        ta.tiles_img = ta.tiles_x * ta.tiles_y;
+        ta.tiles_m = ta.tiles_img * (g.M / (g.OH * g.OW));
+        ta.PWp = c.tw + g.S - 1;
+        ta.patch_len = (c.th + g.R - 1) * ta.PWp;
+    }
     ta.relu = relu ? 1 : 0;
     ta.a_bytes = (unsigned)((size_t)(g.M / (g.OH * g.OW)) * g.IH * g.IW * g.IC * 2);
     ta.w_bytes = (unsigned)wreg_wt_bytes(g);
     ta.dTimg = make_fastdiv((uint32_t)ta.tiles_img);
     ta.dTx = make_fastdiv((uint32_t)ta.tiles_x);
     ta.dPWp = make_fastdiv((uint32_t)ta.PWp);
-    if (TW == 32) return fn == 1 ? launch_tile2d_t<1, 32>(ta, st) : launch_tile2d_t<2, 32>(ta, st);
-    if (TW == 16) return fn == 1 ? launch_tile2d_t<1, 16>(ta, st) : launch_tile2d_t<2, 16>(ta, st);
-    return fn == 1 ? launch_tile2d_t<1, 8>(ta, st) : launch_tile2d_t<2, 8>(ta, st);
+    if (c.variant == 1) return launch_tile2d_t<1, 28, 7, 1>(ta, st);
+    if (c.variant == 2) return launch_tile2d_t<1, 0, 7, 1>(ta, st);
+    const int TW = c.tw;
+    if (TW == 32) return fn == 1 ? launch_tile2d_t<1, 32, 4, 2>(ta, st) : launch_tile2d_t<2, 32, 4, 2>(ta, st);
+    if (TW == 16) return fn == 1 ? launch_tile2d_t<1, 16, 4, 2>(ta, st) : launch_tile2d_t<2, 16, 4, 2>(ta, st);
+    return fn == 1 ? launch_tile2d_t<1, 8, 4, 2>(ta, st) : launch_tile2d_t<2, 8, 4, 2>(ta, st);
 }
 
 }  // namespace wap

@@ -441,7 +441,7 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
     if (cfg == 5 && !wreg_supported(g)) cfg = 0;
     if (g_force_fwd_cfg < 0 && patch_supported(g)) cfg = 6;
     if (cfg == 6 && !patch_supported(g)) cfg = 1;
-    if (g_force_fwd_cfg < 0 && g.Ncols <= 128 && tile2d_supported(g)) cfg = 7;
+    if (g_force_fwd_cfg < 0 && tile2d_preferred(g)) cfg = 7;
     if (cfg == 7 && !tile2d_supported(g)) cfg = 1;
     if (cfg == 6 || cfg == 7) nsplit = 1;
     p.cfg = cfg;

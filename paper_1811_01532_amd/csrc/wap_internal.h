@@ -119,6 +119,7 @@ int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float
 
 // stride-1 convolution on 8 x 32-pixel 2-D tiles for 64 / 128 output channels (conv_tile2d.hip)
 int tile2d_supported(const GemmGeom& g);
+bool tile2d_preferred(const GemmGeom& g);
 const char* tile2d_kernel_name(const GemmGeom& g);
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
                   hipStream_t st, const bf16_t* mask = nullptr);

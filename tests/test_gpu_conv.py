@@ -41,6 +41,9 @@ CASES = [
     ("tile2d_forced_c128_k128", (1, 24, 32, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
     ("tile2d_auto_square_tiles_c64_k64", (2, 32, 48, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("tile2d_forced_square_tiles_c128_k128", (1, 16, 48, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
+    ("tile2d_forced_8x28_strip_tiles_c128_k256", (1, 16, 56, 128, 256, 3, 3, 1, 1), (7, -1, -1)),
+    ("tile2d_forced_flat_tiles_w28_ragged", (3, 28, 28, 128, 256, 3, 3, 1, 1), (7, -1, -1)),
+    ("tile2d_forced_flat_tiles_w14_straddling_images", (5, 14, 14, 64, 128, 3, 3, 1, 1), (7, -1, -1)),
     # patch-in-LDS weight gradient: masked surplus columns (14 -> 16), a forced uneven split, pad 0
     ("wgrad_patch_w14_masked_columns", (3, 14, 14, 128, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("wgrad_patch_w28_forced_split5", (1, 28, 28, 64, 128, 3, 3, 1, 1), (-1, 3, 5)),
