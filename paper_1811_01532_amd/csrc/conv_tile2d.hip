@@ -196,26 +196,53 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel
         }
         __syncthreads();
         const int cs1 = cs + 1 < ncs ? cs + 1 : cs;
+        // Fragment reads run one reduction step ahead of the MFMAs that consume them (two register sets), and the
+        // issue order is pinned: with two or three wavefronts per SIMD the compiler's own order (read, wait, MFMA)
+        // leaves the LDS latency exposed in front of most MFMAs.
+        bf16x8 fa[2][FM];
+#pragma unroll
+        for (int j = 0; j < FM; ++j) fa[0][j] = *reinterpret_cast<const bf16x8*>(smem + frow[j]);
         int r = 0, s = 0;
         for (int tap = 0; tap < RS; ++tap) {
             const bool last = tap + 1 == RS;
+            int s1 = s + 1, r1 = r;
+            if (s1 == g.S) { s1 = 0; r1 = r + 1; }
             const int tapoff = (r * a.PWp + s) * PITCH;
+            const int tapoff1 = last ? tapoff : (r1 * a.PWp + s1) * PITCH;  // after the last tap the read is discarded
+            __builtin_amdgcn_sched_barrier(0);
             load_w(last ? cs1 : cs, last ? 0 : tap + 1, wB);  // one reduction tile ahead (clamped at the very end)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
-                for (int j = 0; j < FM; ++j) {
-                    bf16x8 f = *reinterpret_cast<const bf16x8*>(smem + frow[j] + tapoff + ks * 32);
+                for (int j = 0; j < FM; ++j)
+                    fa[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(
+                        smem + frow[j] + (ks < 3 ? tapoff + (ks + 1) * 32 : tapoff1));
+#pragma unroll
+                for (int j = 0; j < FM; ++j)
 #pragma unroll
                     for (int i = 0; i < FN; ++i)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wA[ks][i], f, acc[i][j], 0, 0, 0);
-                }
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wA[ks][i], fa[ks & 1][j], acc[i][j], 0, 0, 0);
             }
+            // issue order: the 4*FN weight loads ride on the first MFMAs, then one fragment read per FN MFMAs
+            constexpr int NW = 4 * FN < 4 * FM ? 4 * FN : 4 * FM;
+#pragma unroll
+            for (int q = 0; q < NW; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+                __builtin_amdgcn_sched_group_barrier(0x008, FN, 0);  // MFMA
+            }
+#pragma unroll
+            for (int q = 0; q < 4 * FM - NW; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, FN, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
                 for (int i = 0; i < FN; ++i) wA[ks][i] = wB[ks][i];
-            if (++s == g.S) { s = 0; ++r; }
+            r = r1;
+            s = s1;
         }
     }
 
@@ -342,12 +369,13 @@ int tile2d_supported(const GemmGeom& g) {
     return tile_cfg(g).fn;
 }
 
-// Shapes on which this kernel measured faster than conv_patch.hip: thin outputs on 2-D tiles, and the 8 x 28
-// strip tiles (56-pixel-wide maps) at any width; flat tiles only tie with it and stay a forced option.
+// Shapes on which this kernel measured faster than conv_patch.hip: thin outputs on 256-pixel 2-D tiles, and the
+// 224-pixel x 128-channel tiles (8 x 28 strips or flat) at any width once the map is large enough to fill the CUs.
 bool tile2d_preferred(const GemmGeom& g) {
     if (!tile2d_supported(g)) return false;
     const TileCfg c = tile_cfg(g);
-    return (c.variant == 0 && g.Ncols <= 128) || c.variant == 1;
+    if (c.variant == 0) return g.Ncols <= 128;
+    return (long)((g.M + 223) / 224) * (g.Ncols / 128) >= kNumCU * 3 / 4;
 }
 
 const char* tile2d_kernel_name(const GemmGeom& g) {

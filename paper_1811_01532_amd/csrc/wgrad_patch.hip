@@ -171,6 +171,7 @@ __global__ __launch_bounds__(NT, 3) void wgrad_patch_kernel(const WPArgs a) {
         const unsigned char* sB = smem + buf * a.buf_bytes;
         // virtual pixel -> patch row, kept incrementally: 16 pixels further per step, at most one row wrap (VW >= 16)
         int cx0 = col_a, cx1 = col_b, xo0 = xoff_a, xo1 = xoff_b, dof = dfix;
+#pragma unroll 2
         for (int ks = 0; ks < a.nk16; ++ks) {
             const unsigned char* x0 = sB + xo0;
             const unsigned char* x1 = sB + xo1;
