@@ -283,13 +283,10 @@ __global__ __launch_bounds__(NT) void conv_wreg_kernel(const WArgsR a) {
 // lane = (channel % 32) + 32 * (reduction half), zero-filled past the last channel.
 //   flip == 0: forward weights, element (n, kk) = w[n][kk]                       (w is [Ncols][Kred])
 //   flip == 1: data gradient, reduction index kk = (r', s', k): element = w[k][R-1-r'][S-1-s'][n]
-__global__ void pack_weights_kernel(const bf16_t* __restrict__ w, u32x4* __restrict__ Wp, int Ncols, int Kred,
-                                    int IC, int R, int S, int flip) {
+__device__ __forceinline__ void pack_one(const bf16_t* __restrict__ w, u32x4* __restrict__ Wp, int Ncols, int Kred,
+                                         int IC, int R, int S, int flip, size_t v) {
     const int ksteps = Kred / 16;
-    const int nblk = (Ncols + 31) / 32;
-    size_t total = (size_t)nblk * ksteps * 64;
-    size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < total; v += stride) {
+    {
         int lane = (int)(v & 63);
         size_t t = v >> 6;
         int kstep = (int)(t % ksteps);
@@ -317,6 +314,29 @@ __global__ void pack_weights_kernel(const bf16_t* __restrict__ w, u32x4* __restr
     }
 }
 
+__global__ void pack_weights_kernel(const bf16_t* __restrict__ w, u32x4* __restrict__ Wp, int Ncols, int Kred,
+                                    int IC, int R, int S, int flip) {
+    const int ksteps = Kred / 16;
+    const int nblk = (Ncols + 31) / 32;
+    size_t total = (size_t)nblk * ksteps * 64;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < total; v += stride)
+        pack_one(w, Wp, Ncols, Kred, IC, R, S, flip, v);
+}
+
+// Every packing job of a training step in one launch: job j owns the 16-byte vectors [first[j], first[j+1]).
+__global__ void pack_weights_multi_kernel(const PackJobs js, unsigned char* __restrict__ base) {
+    const size_t total = js.first[js.n];
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < total; v += stride) {
+        int j = 0;
+        while (j + 1 < js.n && v >= js.first[j + 1]) ++j;
+        const PackJob& b = js.job[j];
+        pack_one(reinterpret_cast<const bf16_t*>(base + b.w_off), reinterpret_cast<u32x4*>(base + b.out_off), b.Ncols,
+                 b.Kred, b.IC, b.R, b.S, b.flip, v - js.first[j]);
+    }
+}
+
 }  // namespace
 
 bool wreg_supported(const GemmGeom& g) {
@@ -324,6 +344,30 @@ bool wreg_supported(const GemmGeom& g) {
 }
 
 size_t wreg_smem_bytes() { return (size_t)NSTAGE * A_STAGE; }
+
+void pack_jobs_add(PackJobs& js, const GemmGeom& g, bool flip, size_t w_off, size_t out_off) {
+    PackJob& b = js.job[js.n];
+    b.w_off = w_off;
+    b.out_off = out_off;
+    b.Ncols = g.Ncols;
+    b.Kred = g.Kred;
+    b.IC = g.IC;
+    b.R = g.R;
+    b.S = g.S;
+    b.flip = flip ? 1 : 0;
+    if (js.n == 0) js.first[0] = 0;
+    js.first[js.n + 1] = js.first[js.n] + (size_t)((g.Ncols + 31) / 32) * (g.Kred / 16) * 64;
+    ++js.n;
+}
+
+int launch_pack_weights_multi(const PackJobs& js, void* base, hipStream_t st) {
+    if (js.n == 0) return WAP_OK;
+    size_t blocks = (js.first[js.n] + 255) / 256;
+    if (blocks > (size_t)kNumCU * 16) blocks = (size_t)kNumCU * 16;
+    hipLaunchKernelGGL(pack_weights_multi_kernel, dim3((unsigned)blocks), dim3(256), 0, st, js,
+                       reinterpret_cast<unsigned char*>(base));
+    return check_launch("pack_weights_multi");
+}
 
 int launch_pack_weights(const GemmGeom& g, bool flip, const bf16_t* w, void* Wp, hipStream_t st) {
     size_t total = (size_t)((g.Ncols + 31) / 32) * (g.Kred / 16) * 64;

@@ -453,10 +453,11 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
 
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
-                    hipStream_t st, hipEvent_t ev_mid, const bf16_t* relu_mask, hipEvent_t ev_packed) {
+                    hipStream_t st, hipEvent_t ev_mid, const bf16_t* relu_mask, hipEvent_t ev_packed,
+                    const void* prepacked) {
     if (relu_mask && !fwd_like_fuses_mask(g, plan)) {
         // no fused epilogue for this tile configuration: plain product, then the element-wise mask
-        int rc = launch_fwd_like(g, b_tr, plan, A, Bw, bias, relu, out, ws, st, ev_mid, nullptr, ev_packed);
+        int rc = launch_fwd_like(g, b_tr, plan, A, Bw, bias, relu, out, ws, st, ev_mid, nullptr, ev_packed, prepacked);
         if (rc != WAP_OK) return rc;
         return launch_relu_bwd(out, relu_mask, out, (size_t)g.M * g.Ncols, st);
     }
@@ -476,11 +477,15 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
     ka.relu = ka.partial ? 0 : (relu ? 1 : 0);
     ka.out = ka.partial ? ws : (void*)out;
     if (plan.cfg == 6 || plan.cfg == 7) {
-        int rc0 = launch_pack_weights(g, b_tr, Bw, ws, st);
-        if (rc0 != WAP_OK) return rc0;
+        const void* wp = prepacked;
+        if (!wp) {
+            int rc0 = launch_pack_weights(g, b_tr, Bw, ws, st);
+            if (rc0 != WAP_OK) return rc0;
+            wp = ws;
+        }
         if (ev_packed) (void)hipEventRecord(ev_packed, st);
-        return plan.cfg == 6 ? launch_patch(g, A, ws, bias, relu, out, st, relu_mask)
-                             : launch_tile2d(g, A, ws, bias, relu, out, st, relu_mask);
+        return plan.cfg == 6 ? launch_patch(g, A, wp, bias, relu, out, st, relu_mask)
+                             : launch_tile2d(g, A, wp, bias, relu, out, st, relu_mask);
     }
     if (plan.cfg == 5) {
         // the (small) weight tensor is first repacked into MFMA fragment order (taps flipped and

@@ -14,7 +14,7 @@ using namespace wap;
 namespace {
 
 enum OpKind {
-    OP_CONV_FWD, OP_POOL_FWD, OP_FC_FWD, OP_SOFTMAX, OP_RELU_BWD, OP_POOL_BWD,
+    OP_PACK, OP_CONV_FWD, OP_POOL_FWD, OP_FC_FWD, OP_SOFTMAX, OP_RELU_BWD, OP_POOL_BWD,
     OP_FC_DX, OP_FC_DW, OP_CONV_WGRAD, OP_CONV_DGRAD, OP_SGD
 };
 
@@ -32,6 +32,7 @@ struct Op {
     WgradPlan wp;
     bool b_tr = false, relu = false;
     bool has_mask = false;  // data gradient fused with the ReLU derivative of the layer below (mask tensor at t3)
+    bool prepacked = false;  // weights of this operation are repacked once per step by the OP_PACK operation (copy at t4)
     size_t t0 = 0, t1 = 0, t2 = 0, t3 = 0, t4 = 0;  // arena offsets, meaning per kind
     int N = 0, H = 0, W = 0, C = 0, win = 0, st = 0;  // pooling / softmax shapes
     size_t n = 0;
@@ -77,6 +78,7 @@ struct wap_step_plan {
     size_t n_params = 0;
     size_t w32_off = 0, dw_off = 0, wb_off = 0;
     mutable std::vector<hipEvent_t> events;  // cached by wap_step_time
+    PackJobs packjobs = {};                  // every weight repacking of the step, run as one kernel
 
     size_t add(const std::string& name, size_t bytes) {
         size_t off = arena;
@@ -97,13 +99,16 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
            hipEvent_t ev_packed = nullptr) {
     void* ws = base + p->ws_off;
     switch (op.kind) {
+        case OP_PACK:
+            return launch_pack_weights_multi(p->packjobs, base, st);
         case OP_CONV_FWD:
         case OP_FC_FWD:
         case OP_CONV_DGRAD:
         case OP_FC_DX:
             return launch_fwd_like(op.gg, op.b_tr, op.gp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
                                    nullptr, op.relu, (bf16_t*)(base + op.t2), ws, st, ev_mid,
-                                   op.has_mask ? (const bf16_t*)(base + op.t3) : nullptr, ev_packed);
+                                   op.has_mask ? (const bf16_t*)(base + op.t3) : nullptr, ev_packed,
+                                   op.prepacked ? (const void*)(base + op.t4) : nullptr);
         case OP_CONV_WGRAD:
         case OP_FC_DW:
             return launch_wgrad(op.wg, op.wp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
@@ -247,6 +252,12 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         op.bytes = 2.0 * ((double)B * g.IH * g.IW * g.IC + (double)g.Kred * g.Ncols + (double)g.M * g.Ncols);
         op.t0 = a; op.t1 = w; op.t2 = o;
         if (op.gp.ws_bytes > ws_need) ws_need = op.gp.ws_bytes;
+        // kernels that read the weights in MFMA fragment order: one repacking kernel per step serves them all
+        if ((op.gp.cfg == 6 || op.gp.cfg == 7) && p->packjobs.n < kMaxPackJobs) {
+            op.prepacked = true;
+            op.t4 = p->add("wpack." + name, wreg_wt_bytes(g));
+            pack_jobs_add(p->packjobs, g, b_tr, w, op.t4);
+        }
         p->ops.push_back(op);
     };
     auto push_wgrad = [&](OpKind kind, const std::string& name, const WgradGeom& g, size_t x, size_t dy, size_t dw) {
@@ -390,6 +401,13 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         op.bytes = 14.0 * np;
         p->ops.push_back(op);
     }
+    if (p->packjobs.n > 0) {
+        Op op;
+        op.kind = OP_PACK; op.name = "pack_weights";
+        op.kernel = "pack_weights_multi_kernel";
+        op.bytes = 2.0 * 16.0 * (double)p->packjobs.first[p->packjobs.n];
+        p->ops.insert(p->ops.begin(), op);
+    }
     p->ws_bytes = ws_need;
     p->ws_off = p->add("workspace", ws_need ? ws_need : 256);
     *out = p;
@@ -480,7 +498,8 @@ int wap_step_time_masked(const wap_step_plan* p, void* arena, size_t arena_bytes
     };
     auto has_prologue = [&](const Op& op) {
         switch (op.kind) {
-            case OP_CONV_FWD: case OP_FC_FWD: case OP_CONV_DGRAD: case OP_FC_DX: return fwd_like_packs_weights(op.gp);
+            case OP_CONV_FWD: case OP_FC_FWD: case OP_CONV_DGRAD: case OP_FC_DX:
+                return fwd_like_packs_weights(op.gp) && !op.prepacked;
             default: return false;
         }
     };

@@ -73,7 +73,8 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
                     hipStream_t st, hipEvent_t ev_mid = nullptr,  // ev_mid: recorded between kernel and split epilogue
                     const bf16_t* relu_mask = nullptr,   // out = relu_mask > 0 ? out : 0 (same shape as out)
-                    hipEvent_t ev_packed = nullptr);     // recorded after the weight repacking, if the plan has one
+                    hipEvent_t ev_packed = nullptr,      // recorded after the weight repacking, if the plan has one
+                    const void* prepacked = nullptr);    // weights already in packed order: skip the repacking
 bool fwd_like_packs_weights(const GemmPlan& plan);
 bool fwd_like_fuses_mask(const GemmGeom& g, const GemmPlan& plan);  // mask applied in the kernel's own epilogue?
 
@@ -108,6 +109,19 @@ int launch_wgrad_c3(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_
 bool wreg_supported(const GemmGeom& g);
 inline size_t wreg_wt_bytes(const GemmGeom& g) { return (size_t)((g.Ncols + 31) / 32) * 32 * g.Kred * 2; }  // packed copy
 int launch_pack_weights(const GemmGeom& g, bool flip, const bf16_t* w, void* Wp, hipStream_t st);
+// All packing jobs of a launch list in one kernel (offsets are relative to one base pointer).
+struct PackJob {
+    size_t w_off, out_off;  // byte offsets of the source weights and of the packed copy
+    int Ncols, Kred, IC, R, S, flip;
+};
+constexpr int kMaxPackJobs = 32;
+struct PackJobs {
+    int n;
+    size_t first[kMaxPackJobs + 1];  // first 16-byte vector of each job in the concatenated index space
+    PackJob job[kMaxPackJobs];
+};
+void pack_jobs_add(PackJobs& js, const GemmGeom& g, bool flip, size_t w_off, size_t out_off);
+int launch_pack_weights_multi(const PackJobs& js, void* base, hipStream_t st);
 int launch_wreg(const GemmGeom& g, int nsplit, const bf16_t* A, const bf16_t* Bw, const float* bias, bool relu,
                 void* out, bool partial, hipStream_t st);
 
