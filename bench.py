@@ -160,6 +160,9 @@ def main():
     ap.add_argument("--minibatch", type=int, default=64)
     ap.add_argument("--no-table", action="store_true", help="skip the minibatch sweep and per-layer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--link-gbs", type=float, default=76.8,
+                    help="one-direction bandwidth of one xGMI link, GB/s (analytic t_s of the workload analysis)")
+    ap.add_argument("--link-latency-us", type=float, default=10.0, help="latency of one ring step, microseconds")
     ap.add_argument("--table-out", default=None, help="also write the tables as Markdown to this path")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -298,29 +301,81 @@ def main():
                 del bb, p
                 torch.cuda.empty_cache()
         out["util_table"] = table
-        # ---- per-layer table (t_c per pass) of the headline network across the minibatch sweep ----
-        layers = []
-        convs, fcs = si.NETS[net]
+        # ---- per-layer table (t_c per pass) across the minibatch sweep: the headline network in full, the other
+        # one only as input of the workload analysis below ----
         mbs = [8, 16, 32, 64, 128, 256]
-        descs = [(d["name"], 0, wap.conv_desc(1, d["H"], d["W"], d["C"], d["K"], d["R"], d["S"], d["stride"],
-                                              d["pad"], relu=True)) for d in si.conv_shapes(convs, image)]
-        descs += [(name, 1, wap.fc_desc(1, n_in, n_out, relu)) for (name, n_in, n_out, relu) in fcs]
-        for (name, kind, desc) in descs:
-            nbytes = wap.wap_profile_scratch_bytes(kind, desc, mbs)
-            scratch = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
-            rows = wap.wap_profile_layer(kind, desc, mbs, 2, 7, scratch)
-            for r in rows:
-                layers.append({"layer": name, "pass": ("fwd", "dgrad", "wgrad")[r.pass_], "minibatch": r.minibatch,
-                               "us": round(r.time_us_median, 2), "tflops": round(r.tflops, 2),
-                               "frac_peak": round(r.frac_of_bf16_peak, 4), "gbs": round(r.gbytes_per_s, 1),
-                               "bound": ("mfma", "hbm")[r.bound]})
-            del scratch
-            torch.cuda.empty_cache()
+
+        def layer_table(tnet):
+            rows_out = []
+            convs, fcs = si.NETS[tnet]
+            descs = [(d["name"], 0, d["K"] * d["R"] * d["S"] * d["C"],
+                      wap.conv_desc(1, d["H"], d["W"], d["C"], d["K"], d["R"], d["S"], d["stride"], d["pad"], relu=True))
+                     for d in si.conv_shapes(convs, image)]
+            descs += [(name, 1, n_in * n_out, wap.fc_desc(1, n_in, n_out, relu)) for (name, n_in, n_out, relu) in fcs]
+            for (name, kind, nparam, desc) in descs:
+                nbytes = wap.wap_profile_scratch_bytes(kind, desc, mbs)
+                scratch = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+                rows = wap.wap_profile_layer(kind, desc, mbs, 2, 7, scratch)
+                for r in rows:
+                    rows_out.append({"layer": name, "pass": ("fwd", "dgrad", "wgrad")[r.pass_], "minibatch": r.minibatch,
+                                     "us": round(r.time_us_median, 2), "tflops": round(r.tflops, 2),
+                                     "frac_peak": round(r.frac_of_bf16_peak, 4), "gbs": round(r.gbytes_per_s, 1),
+                                     "bound": ("mfma", "hbm")[r.bound], "params": nparam})
+                del scratch
+                torch.cuda.empty_cache()
+            return rows_out
+
+        tables = {net: layer_table(net)}
+        other = "alexnet" if net == "vgg16" else "vgg16"
+        tables[other] = layer_table(other)
+        layers = [{k: v for k, v in r.items() if k != "params"} for r in tables[net]]
         out["layers"] = layers
+
+        # ---- workload analysis (Eq. 1): t_c(l, d) from the table at per-GPU minibatch B/d (forward + both
+        # backward passes; no data gradient for the first layer), t_s from the ring all-reduce model over one
+        # xGMI link; d restricted to the divisions of the global minibatch that the sweep measured ----
+        link_bw, link_lat = a.link_gbs * 1e9, a.link_latency_us * 1e-6
+        wau_rows = []
+        for tnet, rows in tables.items():
+            names = []
+            for r in rows:
+                if r["layer"] not in names:
+                    names.append(r["layer"])
+            t_of = {(r["layer"], r["pass"], r["minibatch"]): r["us"] * 1e-6 for r in rows}
+            params = {r["layer"]: r["params"] for r in rows}
+            for Bg in (64, 128, 256):
+                G = 8
+                allowed = [1 if (Bg % d == 0 and Bg // d in mbs) else 0 for d in range(1, G + 1)]
+                t_c = []
+                for li, name in enumerate(names):
+                    row = []
+                    for d in range(1, G + 1):
+                        if not allowed[d - 1]:
+                            row.append(0.0)
+                            continue
+                        b = Bg // d
+                        t = t_of[(name, "fwd", b)] + t_of[(name, "wgrad", b)]
+                        if li > 0:
+                            t += t_of[(name, "dgrad", b)]
+                        row.append(t)
+                    t_c.append(row)
+                gb = [4.0 * params[n] for n in names]
+                best, est = wap.wap_choose_gpus(t_c, gb, link_bw, link_lat, allowed)
+                wau_rows.append({"net": tnet, "global_minibatch": Bg, "best_d": best,
+                                 "t_estimate_ms": {str(d): round(est[d - 1] * 1e3, 4) for d in range(1, G + 1) if allowed[d - 1]},
+                                 "images_per_s": {str(d): round(Bg / est[d - 1], 1) for d in range(1, G + 1) if allowed[d - 1]}})
+        out["wau"] = {"link_bytes_per_s": link_bw, "latency_s": link_lat,
+                      "note": "t_c measured on this GPU at minibatch B/d (wap_profile_layer); t_s analytic (ring all-reduce "
+                              "over one xGMI link, fp32 gradients); no multi-GPU run is involved",
+                      "decisions": wau_rows}
         md.append("| net | minibatch | ms/step | TFLOP/s | frac of bf16 peak | images/s |\n|---|---|---|---|---|---|")
         for r in table:
             md.append(f"| {r['net']} | {r['minibatch']} | {r['ms_per_step']} | {r['tflops']} | "
                       f"{r['frac_of_bf16_peak']} | {r['images_per_s']} |")
+        md.append("\n| net | global minibatch | t_estimate ms by d | chosen d |\n|---|---|---|---|")
+        for r in wau_rows:
+            md.append(f"| {r['net']} | {r['global_minibatch']} | "
+                      + ", ".join(f"d={d}: {t}" for d, t in r["t_estimate_ms"].items()) + f" | {r['best_d']} |")
         md.append("\n| layer | pass | minibatch | us | TFLOP/s | frac of peak | GB/s | side of ridge |\n|---|---|---|---|---|---|---|---|")
         for r in layers:
             md.append(f"| {r['layer']} | {r['pass']} | {r['minibatch']} | {r['us']} | {r['tflops']} | "

@@ -181,6 +181,27 @@ int wap_profile_layer(int kind, const void* desc, const int32_t* minibatches, in
                       int32_t warmup, int32_t iters, void* scratch, size_t scratch_bytes,
                       void* stream, wap_profile_row* rows_out, int32_t rows_cap, int32_t* rows_written);
 
+/* ---- the workload analysis unit's decision (Section 3.2.1): how many GPUs to divide the workload over ----
+ * Evaluates Eq. 1, t_estimate(d) = sum over layers of { t_c(l, d) + t_s(l, d) }, for d = 1..max_gpus and
+ * returns the d with the smallest estimate.  Host arithmetic only (fp64); no device work, no stream.
+ *   t_c          host, [n_layers][max_gpus] seconds: entry (l, d-1) is the forward + backward time of layer l
+ *                at the divided workload (per-GPU minibatch B/d), e.g. summed from wap_profile_layer rows;
+ *   grad_bytes   host, [n_layers]: bytes of layer l's weight gradient (what the aggregation moves);
+ *   link         ring all-reduce model of Section 3.2.3: t_s(l, d) = 0 for d = 1, otherwise
+ *                2 (d-1)/d * grad_bytes[l] / link_bytes_per_s + 2 (d-1) * latency_s;
+ *   allowed      host, [max_gpus] or NULL: non-zero where d is a usable division (e.g. d divides the minibatch);
+ *   t_estimate_out  host, [max_gpus]: the estimates (+infinity where d is not allowed);
+ *   best_d_out   the minimiser; an exact tie goes to the smaller d (fewer GPUs for the same time).
+ * WAP_EINVAL for NULL / non-positive sizes, negative or non-finite times or bytes, a non-positive bandwidth,
+ * a negative latency, or no allowed d. */
+typedef struct {
+    double link_bytes_per_s;
+    double latency_s;
+} wap_link_model;
+int wap_choose_gpus(int32_t n_layers, int32_t max_gpus, const double* t_c, const double* grad_bytes,
+                    const wap_link_model* link, const uint8_t* allowed, double* t_estimate_out,
+                    int32_t* best_d_out);
+
 /* ---- whole training step of one replica: forward, loss, backward, SGD (host-side launch list) ---- */
 typedef struct wap_step_plan wap_step_plan;
 

@@ -201,6 +201,23 @@ def wap_profile_layer(kind, desc, minibatches, warmup, iters, scratch, stream=No
     return [rows[i] for i in range(written.value)]
 
 
+class LinkModel(ctypes.Structure):
+    _fields_ = [("link_bytes_per_s", ctypes.c_double), ("latency_s", ctypes.c_double)]
+
+
+def wap_choose_gpus(t_c, grad_bytes, link_bytes_per_s, latency_s, allowed=None):
+    """t_c: n_layers rows of max_gpus seconds; returns (best d, [t_estimate(d) for d = 1..max_gpus])."""
+    n_layers, max_gpus = len(t_c), len(t_c[0])
+    flat = (ctypes.c_double * (n_layers * max_gpus))(*[float(v) for row in t_c for v in row])
+    gb = (ctypes.c_double * n_layers)(*[float(v) for v in grad_bytes])
+    link = LinkModel(float(link_bytes_per_s), float(latency_s))
+    mask = None if allowed is None else (ctypes.c_uint8 * max_gpus)(*[1 if a else 0 for a in allowed])
+    est = (ctypes.c_double * max_gpus)()
+    best = ctypes.c_int32(0)
+    _check(lib().wap_choose_gpus(n_layers, max_gpus, flat, gb, ctypes.byref(link), mask, est, ctypes.byref(best)))
+    return best.value, [float(est[i]) for i in range(max_gpus)]
+
+
 class StepPlan:
     """Host-side launch list of one replica's training step (wap_step_plan_*)."""
 
