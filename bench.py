@@ -188,6 +188,15 @@ def main():
     ops = plan.ops()
     flops_step = plan.flops()
 
+    # Untimed: three plain device-to-device copies of a known size (256 MiB); they appear in a rocprofv3 counter run
+    # as the runtime's copy kernel and calibrate FETCH_SIZE / WRITE_SIZE (see profiles/).
+    cal_src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    for _ in range(3):
+        cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+    torch.cuda.empty_cache()
     # Untimed, before the warm-up: two plain steps, then one step with an event pair around every operation.
     # That pass gives the per-operation breakdown and names the kernel with the largest share of the step.
     for _ in range(2):
