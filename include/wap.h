@@ -87,6 +87,17 @@ int wap_conv2d_workspace_bytes(const wap_conv_desc* d, int pass, size_t* bytes_o
 int wap_conv2d_fwd(const wap_conv_desc* d, const void* x, const void* w, const float* bias,
                    void* y, void* ws, size_t ws_bytes, void* stream);
 
+/* Convolution forward followed by a 2x2 / stride-2 max-pool of its (bias / ReLU applied) output, the
+ * conv -> ReLU -> pool chain of a VGG block (primary node plus its auxiliary nodes, Section 3.2.2):
+ * y_pool[n,p/2,q/2,k] and argmax (uint8, r*2+s of the first maximum in window scan order) exactly as
+ * wap_conv2d_fwd followed by wap_maxpool_fwd(win 2, stride 2) would produce them.  P and Q must be even.
+ * Where the tile kernel allows it (wap_conv2d_fwd_pool2x2_fused reports 1) the pool is taken from the
+ * convolution's own epilogue and y may be NULL (the full-size output is then never written); otherwise
+ * y is required and the two kernels run back to back. */
+int wap_conv2d_fwd_pool2x2(const wap_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
+                           void* y_pool, uint8_t* argmax, void* ws, size_t ws_bytes, void* stream);
+int wap_conv2d_fwd_pool2x2_fused(const wap_conv_desc* d, int32_t* fused_out);
+
 /* dx[n,h,w,c] = sum_{k,r,s} dy[n,p,q,k] * w[k,r,s,c] over the (p,q) whose tap (r,s) reads (h,w).
  * dy: bf16 [N][P][Q][K]; dx: bf16 [N][H][W][C], every element written (zeros where the forward
  * pass never reads). */

@@ -129,6 +129,17 @@ def wap_conv2d_fwd(desc, x, w, bias, y, ws=None, stream=None):
                                 ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
 
 
+def wap_conv2d_fwd_pool2x2(desc, x, w, bias, y, y_pool, argmax, ws=None, stream=None):
+    _check(lib().wap_conv2d_fwd_pool2x2(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _ptr(y_pool),
+                                        _ptr(argmax), _ptr(ws), ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
+
+
+def wap_conv2d_fwd_pool2x2_fused(desc):
+    out = ctypes.c_int32(0)
+    _check(lib().wap_conv2d_fwd_pool2x2_fused(ctypes.byref(desc), ctypes.byref(out)))
+    return bool(out.value)
+
+
 def wap_conv2d_bwd_data(desc, dy, w, dx, ws=None, stream=None):
     _check(lib().wap_conv2d_bwd_data(ctypes.byref(desc), _ptr(dy), _ptr(w), _ptr(dx), _ptr(ws),
                                      ctypes.c_size_t(_nbytes(ws)), _stream(stream)))

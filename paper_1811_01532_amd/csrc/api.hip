@@ -179,6 +179,36 @@ int wap_conv2d_fwd(const wap_conv_desc* d, const void* x, const void* w, const f
                            (bf16_t*)y, ws, (hipStream_t)stream);
 }
 
+int wap_conv2d_fwd_pool2x2_fused(const wap_conv_desc* d, int32_t* fused_out) {
+    WAP_TRY(validate_conv(d));
+    if (!fused_out) return set_error(WAP_EINVAL, "fwd_pool2x2_fused: NULL argument");
+    GemmGeom g = geom_conv_fwd(*d);
+    *fused_out = fwd_like_fuses_pool(g, plan_fwd_like(g, false)) ? 1 : 0;
+    return WAP_OK;
+}
+
+int wap_conv2d_fwd_pool2x2(const wap_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
+                           void* y_pool, uint8_t* argmax, void* ws, size_t ws_bytes, void* stream) {
+    WAP_TRY(validate_conv(d));
+    WAP_TRY(check_ptr(x, "x"));
+    WAP_TRY(check_ptr(w, "w"));
+    WAP_TRY(check_ptr(y_pool, "y_pool"));
+    WAP_TRY(check_ptr(argmax, "argmax"));
+    GemmGeom g = geom_conv_fwd(*d);
+    if ((g.OH & 1) || (g.OW & 1)) return set_error(WAP_EINVAL, "fwd_pool2x2: output size %dx%d is not even", g.OH, g.OW);
+    GemmPlan p = plan_fwd_like(g, false);
+    WAP_TRY(check_ws(p.ws_bytes, ws, ws_bytes));
+    const bool relu = (d->flags & WAP_RELU) != 0;
+    if (fwd_like_fuses_pool(g, p))
+        return launch_fwd_like(g, false, p, (const bf16_t*)x, (const bf16_t*)w, bias, relu, (bf16_t*)y, ws,
+                               (hipStream_t)stream, nullptr, nullptr, nullptr, nullptr, (bf16_t*)y_pool, argmax);
+    if (!y) return set_error(WAP_EINVAL, "fwd_pool2x2: this shape is not fused, y is required");
+    WAP_TRY(launch_fwd_like(g, false, p, (const bf16_t*)x, (const bf16_t*)w, bias, relu, (bf16_t*)y, ws,
+                            (hipStream_t)stream));
+    return launch_maxpool_fwd(d->N, g.OH, g.OW, d->K, 2, 2, (const bf16_t*)y, (bf16_t*)y_pool, argmax,
+                              (hipStream_t)stream);
+}
+
 int wap_conv2d_bwd_data(const wap_conv_desc* d, const void* dy, const void* w, void* dx, void* ws,
                         size_t ws_bytes, void* stream) {
     WAP_TRY(validate_conv(d));

@@ -31,7 +31,9 @@ struct TArgs {
     const bf16_t* Wp;  // packed weights
     const float* bias;
     const bf16_t* mask;  // optional: out = mask > 0 ? out : 0
-    bf16_t* out;
+    bf16_t* out;         // may be NULL when only the pooled output is wanted
+    bf16_t* pool_y;      // optional (2-D 256-pixel tiles only): 2x2 / stride-2 max-pool of the output tile ...
+    uint8_t* pool_am;    // ... and the position r*2+s of the first maximum of every window
     GemmGeom g;
     int tiles_x, tiles_y, tiles_img, tiles_m, tiles_n;
     int PWp, patch_len;  // padded tile (flat tiles: image) width, padded pixels per patch (2-D tiles)
@@ -296,7 +298,45 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel
             u32x4 vv = *reinterpret_cast<const u32x4*>(smem + row * OPITCH + (tid % VPR) * 16);
             const size_t o = (size_t)m * g.Ncols + n0 + (tid % VPR) * 8;
             if (a.mask) vv = relu_mask8(vv, *reinterpret_cast<const u32x4*>(a.mask + o));
-            *reinterpret_cast<u32x4*>(a.out + o) = vv;
+            if (a.out) *reinterpret_cast<u32x4*>(a.out + o) = vv;
+        }
+        // ---- fused 2x2 / stride-2 max-pool of the staged (bias / ReLU applied, bf16) tile: tile origin and size
+        // are even, and both rows of a window are staged in the same pass (a 32-pixel fragment holds whole tile
+        // rows and passes hold fragment pairs).  Same rule as maxpool_fwd_kernel: first maximum in (r, s) order. ----
+        if (!FLAT && PG == 2 && FM == 4 && a.pool_y) {
+            constexpr int PWT = TWD / 2;  // pooled pixels per tile row
+            auto srow_of = [&](int idx) {
+                const int f = idx >> 5;
+                return ((f / FM) * JN + (f % FM) - half * JN) * 32 + (idx & 31);
+            };
+            for (int item = tid; item < (BM / 4) * VPR; item += NT) {
+                const int pp = item / VPR, vec = item % VPR;
+                const int py = pp / PWT, px = pp % PWT;
+                const int idx00 = (2 * py) * TWD + 2 * px;
+                if ((((idx00 >> 5) % FM) / JN) != half) continue;  // window staged in the other pass
+                const int idx4[4] = {idx00, idx00 + 1, idx00 + TWD, idx00 + TWD + 1};
+                unsigned short best[8];
+                float bestf[8];
+                unsigned char bi[8];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(smem + srow_of(idx4[k]) * OPITCH + vec * 16);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const unsigned short bits = (unsigned short)((e & 1) ? (v[e >> 1] >> 16) : (v[e >> 1] & 0xffffu));
+                        const float f = __uint_as_float((unsigned)bits << 16);
+                        if (k == 0 || f > bestf[e]) { bestf[e] = f; best[e] = bits; bi[e] = (unsigned char)k; }
+                    }
+                }
+                const size_t po = ((size_t)(img * (g.OH / 2) + oh0 / 2 + py) * (g.OW / 2) + ow0 / 2 + px) * g.Ncols + n0 + vec * 8;
+                u32x4 yo = {(unsigned)best[0] | ((unsigned)best[1] << 16), (unsigned)best[2] | ((unsigned)best[3] << 16),
+                            (unsigned)best[4] | ((unsigned)best[5] << 16), (unsigned)best[6] | ((unsigned)best[7] << 16)};
+                *reinterpret_cast<u32x4*>(a.pool_y + po) = yo;
+                uint2 am;
+                am.x = bi[0] | (bi[1] << 8) | (bi[2] << 16) | ((unsigned)bi[3] << 24);
+                am.y = bi[4] | (bi[5] << 8) | (bi[6] << 16) | ((unsigned)bi[7] << 24);
+                *reinterpret_cast<uint2*>(a.pool_am + po) = am;
+            }
         }
     }
 }
@@ -388,10 +428,21 @@ const char* tile2d_kernel_name(const GemmGeom& g) {
     return names[c.fn == 2 ? 1 : 0][c.tw == 32 ? 0 : c.tw == 16 ? 1 : 2];
 }
 
+// can the epilogue also emit the 2x2 / stride-2 max-pool of the output?
+bool tile2d_fuses_pool(const GemmGeom& g) {
+    if (!tile2d_supported(g)) return false;
+    return tile_cfg(g).variant == 0;  // even tile origin and size, whole windows per staging pass
+}
+
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                  hipStream_t st, const bf16_t* mask) {
+                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am) {
     TArgs ta = {};
     ta.mask = mask;
+    if ((pool_y || pool_am) && !(pool_y && pool_am && tile2d_fuses_pool(g)))
+        return set_error(WAP_EINVAL, "internal: fused pooling not available for this shape");
+    if (!out && !pool_y) return set_error(WAP_EINVAL, "internal: no output");
+    ta.pool_y = pool_y;
+    ta.pool_am = pool_am;
     if (!tile2d_supported(g)) return set_error(WAP_EINVAL, "internal: 2-D tile kernel not applicable");
     const TileCfg c = tile_cfg(g);
     const int fn = c.fn;

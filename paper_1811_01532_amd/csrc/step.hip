@@ -33,7 +33,8 @@ struct Op {
     bool b_tr = false, relu = false;
     bool has_mask = false;  // data gradient fused with the ReLU derivative of the layer below (mask tensor at t3)
     bool prepacked = false;  // weights of this operation are repacked once per step by the OP_PACK operation (copy at t4)
-    size_t t0 = 0, t1 = 0, t2 = 0, t3 = 0, t4 = 0;  // arena offsets, meaning per kind
+    size_t t0 = 0, t1 = 0, t2 = 0, t3 = 0, t4 = 0, t5 = 0;  // arena offsets, meaning per kind
+    bool has_pool = false;  // conv forward whose epilogue also emits the 2x2 max-pool (y_pool at t3, argmax at t5)
     int N = 0, H = 0, W = 0, C = 0, win = 0, st = 0;  // pooling / softmax shapes
     size_t n = 0;
     const char* kernel = "";  // kernel instantiation the operation launches
@@ -106,9 +107,11 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
         case OP_CONV_DGRAD:
         case OP_FC_DX:
             return launch_fwd_like(op.gg, op.b_tr, op.gp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
-                                   nullptr, op.relu, (bf16_t*)(base + op.t2), ws, st, ev_mid,
+                                   nullptr, op.relu, op.has_pool ? nullptr : (bf16_t*)(base + op.t2), ws, st, ev_mid,
                                    op.has_mask ? (const bf16_t*)(base + op.t3) : nullptr, ev_packed,
-                                   op.prepacked ? (const void*)(base + op.t4) : nullptr);
+                                   op.prepacked ? (const void*)(base + op.t4) : nullptr,
+                                   op.has_pool ? (bf16_t*)(base + op.t3) : nullptr,
+                                   op.has_pool ? (uint8_t*)(base + op.t5) : nullptr);
         case OP_CONV_WGRAD:
         case OP_FC_DW:
             return launch_wgrad(op.wg, op.wp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
@@ -282,7 +285,18 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         double f = 2.0 * g.M * (double)g.Ncols * g.Kred;
         flops += (i == 0 ? 2.0 : 3.0) * f;
         cur = conv_y[i];
-        if (convs[i].pool_win) {
+        // conv -> ReLU -> 2x2 pool: where the conv kernel can pool in its own epilogue the full-size output is never
+        // written (the backward pass needs only the pooled activations and the argmax); the kept-gradients layout
+        // keeps the two operations apart for inspection
+        if (convs[i].pool_win == 2 && convs[i].pool_st == 2 && !keep && fwd_like_fuses_pool(g, p->ops.back().gp)) {
+            Op& cf = p->ops.back();
+            cf.has_pool = true;
+            cf.t3 = pool_y[i];
+            cf.t5 = pool_am[i];
+            cf.name = lname(i) + ".fwd+pool";
+            cf.bytes += 3.0 * pool_y_elems[i] - 2.0 * conv_y_elems[i];
+            cur = pool_y[i];
+        } else if (convs[i].pool_win) {
             Op op;
             op.kind = OP_POOL_FWD; op.name = lname(i) + ".pool.fwd";
             op.N = B; op.H = g.OH; op.W = g.OW; op.C = d.K; op.win = convs[i].pool_win; op.st = convs[i].pool_st;

@@ -74,7 +74,10 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
                     hipStream_t st, hipEvent_t ev_mid = nullptr,  // ev_mid: recorded between kernel and split epilogue
                     const bf16_t* relu_mask = nullptr,   // out = relu_mask > 0 ? out : 0 (same shape as out)
                     hipEvent_t ev_packed = nullptr,      // recorded after the weight repacking, if the plan has one
-                    const void* prepacked = nullptr);    // weights already in packed order: skip the repacking
+                    const void* prepacked = nullptr,     // weights already in packed order: skip the repacking
+                    bf16_t* pool_y = nullptr,            // 2x2 / stride-2 max-pool of the output from the same epilogue
+                    uint8_t* pool_am = nullptr);         // (only where fwd_like_fuses_pool; `out` may then be NULL)
+bool fwd_like_fuses_pool(const GemmGeom& g, const GemmPlan& plan);
 bool fwd_like_packs_weights(const GemmPlan& plan);
 bool fwd_like_fuses_mask(const GemmGeom& g, const GemmPlan& plan);  // mask applied in the kernel's own epilogue?
 
@@ -136,7 +139,8 @@ int tile2d_supported(const GemmGeom& g);
 bool tile2d_preferred(const GemmGeom& g);
 const char* tile2d_kernel_name(const GemmGeom& g);
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                  hipStream_t st, const bf16_t* mask = nullptr);
+                  hipStream_t st, const bf16_t* mask = nullptr, bf16_t* pool_y = nullptr, uint8_t* pool_am = nullptr);
+bool tile2d_fuses_pool(const GemmGeom& g);
 
 const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan);
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan);

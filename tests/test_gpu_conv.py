@@ -97,6 +97,23 @@ def test_conv_three_passes_match_oracle(orc, name, shape, force):
         e = gu.rel_err(got2, ref2)
         assert e <= gu.TOL and e <= gu.TOL_BF16_OUT, f"fwd+bias+relu rel err {e}"
         assert np.all(got2 >= 0.0)
+        # ---- forward + 2x2 max-pool in one call: the oracle's pool of the device's own conv output (teacher
+        # forcing) bit for bit; where the kernel pools in its epilogue, also without the full-size output ----
+        if P % 2 == 0 and Q % 2 == 0:
+            yp = torch.full((N, P // 2, Q // 2, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+            am = torch.full((N, P // 2, Q // 2, K), 77, dtype=torch.uint8, device="cuda")
+            y3 = torch.full((N, P, Q, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+            wap.wap_conv2d_fwd_pool2x2(d2, xd, wd, bd, y3, yp, am, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(y3, y2)
+            ref_p, ref_am = orc.maxpool_fwd(got2, 2, 2)
+            assert np.array_equal(gu.host_f64(yp), ref_p) and np.array_equal(am.cpu().numpy(), ref_am)
+            if wap.wap_conv2d_fwd_pool2x2_fused(d2):
+                yp2 = torch.full_like(yp, float("nan"))
+                am2 = torch.full_like(am, 77)
+                wap.wap_conv2d_fwd_pool2x2(d2, xd, wd, bd, None, yp2, am2, ws)
+                torch.cuda.synchronize()
+                assert torch.equal(yp2, yp) and torch.equal(am2, am)
         # ---- data gradient ----
         dx = torch.full((N, H, W, C), float("nan"), dtype=torch.bfloat16, device="cuda")
         ws = gu.workspace(wap.wap_conv2d_workspace_bytes(d, wap.WAP_PASS_BWD_DATA))
