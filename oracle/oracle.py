@@ -173,6 +173,16 @@ def fc_bwd_weight(dy, x):
     return dW
 
 
+def bias_grad(dy):
+    """db[k] = sum of dy over every axis but the last (channels)."""
+    dy = _f64(dy)
+    cols = dy.shape[-1]
+    rows = dy.size // cols
+    db = np.empty(cols, dtype=np.float64)
+    lib().orc_bias_grad(_d(dy), _d(db), ctypes.c_int64(rows), ctypes.c_int64(cols))
+    return db
+
+
 def relu_bwd(dy, y):
     dy, y = _f64(dy), _f64(y)
     dx = np.empty_like(dy)

@@ -219,6 +219,16 @@ void orc_fc_bwd_weight(const double* dy, const double* x, double* dW, int B, int
         }
 }
 
+/* ---- bias gradient of a layer y = act(conv(x, w) + bias[k]) (or FC): the bias is added to every output
+ *      pixel / row of channel k, so db[k] = sum over rows r of dy[r][k], dy viewed as [rows][cols] ---- */
+void orc_bias_grad(const double* dy, double* db, int64_t rows, int64_t cols) {
+    for (int64_t c = 0; c < cols; ++c) {
+        double s = 0.0;
+        for (int64_t r = 0; r < rows; ++r) s += dy[r * cols + c];
+        db[c] = s;
+    }
+}
+
 /* ---- ReLU backward; the derivative at zero is taken as zero: dx = dy where y > 0 ---- */
 void orc_relu_bwd(const double* dy, const double* y, double* dx, int64_t n) {
     for (int64_t i = 0; i < n; ++i) dx[i] = (y[i] > 0.0) ? dy[i] : 0.0;

@@ -185,3 +185,23 @@ def test_input_recipe_is_seeded_and_counts_match(orc):
     assert params("vgg16") == 138357544 - (64 * 2 + 128 * 2 + 256 * 3 + 512 * 6 + 4096 * 2 + 1000)
     assert abs(si.step_flops_per_image("alexnet") / 1e9 - 4.145) < 0.01
     assert abs(si.step_flops_per_image("vgg16") / 1e9 - 92.65) < 0.05
+
+
+def test_bias_grad_is_the_derivative_of_the_loss_wrt_the_bias(orc):
+    """Pins: (a) finite differences of <conv(x, w) + b, dy> in b; (b) all-ones dy gives the pixel count;
+    (c) the adjoint identity <broadcast(b), dy> = <b, db>."""
+    g = np.random.default_rng(31)
+    x, w = g.standard_normal((2, 5, 6, 3)), g.standard_normal((4, 3, 3, 3))
+    b = g.standard_normal(4)
+    y0 = orc.conv2d_fwd(x, w, (1, 1), (1, 1), bias=b)
+    dy = g.standard_normal(y0.shape)
+    db = orc.bias_grad(dy)
+    eps = 1e-6
+    for k in range(4):
+        bp = b.copy(); bp[k] += eps
+        num = (np.sum(orc.conv2d_fwd(x, w, (1, 1), (1, 1), bias=bp) * dy) - np.sum(y0 * dy)) / eps
+        assert abs(num - db[k]) <= 1e-6 * max(1.0, abs(db[k]))
+    assert np.array_equal(orc.bias_grad(np.ones((3, 4, 5, 7))), np.full(7, 60.0))
+    assert np.isclose(np.sum(np.broadcast_to(b, dy.shape) * dy), np.dot(b, db), rtol=1e-13)
+    # plain definition on a 2-D view
+    assert np.allclose(db, dy.reshape(-1, 4).sum(axis=0), rtol=0, atol=1e-12)
