@@ -134,6 +134,13 @@ int wap_fc_bwd(const wap_fc_desc* d, const void* x, const void* Wt, const void* 
  *      (Section 3.2.3).  The paper names them without formulas; the definitions are the
  *      standard ones, with the tie and zero-point rules stated here. ---- */
 
+/* Bias gradient of a primary node whose epilogue adds bias[k] to every output pixel (rows = N*P*Q) or batch
+ * row (rows = B) of channel k:  db[k] = sum over rows of dy[row][k].  dy: bf16 device [rows][cols];
+ * db: fp32 device [cols]; ws: device scratch of wap_bias_grad_workspace_bytes.  Two-stage reduction in a
+ * fixed order: bitwise reproducible. */
+int wap_bias_grad_workspace_bytes(int64_t rows, int32_t cols, size_t* bytes_out);
+int wap_bias_grad(int64_t rows, int32_t cols, const void* dy, float* db, void* ws, size_t ws_bytes, void* stream);
+
 /* dx[i] = y[i] > 0 ? dy[i] : 0  (derivative at zero is zero).  bf16, n elements; dx may alias dy. */
 int wap_relu_bwd(const void* dy, const void* y, void* dx, int64_t n, void* stream);
 

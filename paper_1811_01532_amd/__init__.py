@@ -169,6 +169,17 @@ def wap_relu_bwd(dy, y, dx, n, stream=None):
     _check(lib().wap_relu_bwd(_ptr(dy), _ptr(y), _ptr(dx), ctypes.c_int64(n), _stream(stream)))
 
 
+def wap_bias_grad_workspace_bytes(rows, cols):
+    out = ctypes.c_size_t(0)
+    _check(lib().wap_bias_grad_workspace_bytes(ctypes.c_int64(rows), int(cols), ctypes.byref(out)))
+    return out.value
+
+
+def wap_bias_grad(rows, cols, dy, db, ws, stream=None):
+    _check(lib().wap_bias_grad(ctypes.c_int64(rows), int(cols), _ptr(dy), _ptr(db), _ptr(ws),
+                               ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
+
+
 def wap_maxpool_fwd(N, H, W, C, win, st, x, y, argmax, stream=None):
     _check(lib().wap_maxpool_fwd(N, H, W, C, win, st, _ptr(x), _ptr(y), _ptr(argmax), _stream(stream)))
 

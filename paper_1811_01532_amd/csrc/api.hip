@@ -300,6 +300,23 @@ int wap_fc_bwd(const wap_fc_desc* d, const void* x, const void* Wt, const void* 
     return WAP_OK;
 }
 
+int wap_bias_grad_workspace_bytes(int64_t rows, int32_t cols, size_t* bytes_out) {
+    if (!bytes_out) return set_error(WAP_EINVAL, "bias_grad: NULL argument");
+    if (rows < 1 || cols < 1) return set_error(WAP_EINVAL, "bias_grad: rows and cols must be >= 1");
+    if ((long long)rows * cols > kMaxElems) return set_error(WAP_EUNSUPPORTED, "bias_grad: tensor exceeds 2^31-1 elements");
+    *bytes_out = (size_t)bias_grad_chunks((size_t)rows, cols) * cols * sizeof(float);
+    return WAP_OK;
+}
+
+int wap_bias_grad(int64_t rows, int32_t cols, const void* dy, float* db, void* ws, size_t ws_bytes, void* stream) {
+    size_t need = 0;
+    WAP_TRY(wap_bias_grad_workspace_bytes(rows, cols, &need));
+    WAP_TRY(check_ptr(dy, "dy"));
+    WAP_TRY(check_ptr(db, "db"));
+    WAP_TRY(check_ws(need, ws, ws_bytes));
+    return launch_bias_grad((size_t)rows, cols, (const bf16_t*)dy, db, (float*)ws, (hipStream_t)stream);
+}
+
 int wap_relu_bwd(const void* dy, const void* y, void* dx, int64_t n, void* stream) {
     if (n < 1) return set_error(WAP_EINVAL, "relu_bwd: n must be >= 1");
     WAP_TRY(check_ptr(dy, "dy"));

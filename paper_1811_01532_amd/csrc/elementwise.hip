@@ -122,6 +122,54 @@ __global__ __launch_bounds__(256) void reduce_f32_grouped_kernel(const float* __
     }
 }
 
+// ---- bias gradient, first stage: column sums of a chunk of rows.  A thread owns one 8-channel vector (or one
+// channel) and every RP-th row of the chunk; the RP partial sums per column are then added in thread order. ----
+template <int VEC>
+__global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict__ dy, float* __restrict__ part,
+                                                        size_t rows, int cols, size_t rows_per_chunk) {
+    __shared__ float red[256][VEC + 1];
+    const int cv = (cols + VEC - 1) / VEC;         // vectors per row
+    const int vpb = cv < 256 ? cv : 256;           // vectors handled side by side by this work-group
+    const int rp = 256 / vpb;                      // rows in flight per pass
+    const int vec = threadIdx.x % vpb, rsub = threadIdx.x / vpb;
+    const size_t r0 = (size_t)blockIdx.x * rows_per_chunk;
+    size_t r1 = r0 + rows_per_chunk;
+    if (r1 > rows) r1 = rows;
+    for (int v0 = 0; v0 < cv; v0 += vpb) {
+        const int v = v0 + vec;
+        float s[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s[e] = 0.f;
+        if (rsub < rp && v < cv) {
+            for (size_t r = r0 + rsub; r < r1; r += rp) {
+                if (VEC == 8) {
+                    const uint4 u = *reinterpret_cast<const uint4*>(dy + r * cols + (size_t)v * 8);
+                    const unsigned w4[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        s[2 * k] += __uint_as_float(w4[k] << 16);
+                        s[2 * k + 1] += __uint_as_float(w4[k] & 0xffff0000u);
+                    }
+                } else {
+                    s[0] += bf2f(dy[r * cols + v]);
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) red[threadIdx.x][e] = s[e];
+        __syncthreads();
+        if (rsub == 0 && v < cv) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                float t = red[vec][e];
+                for (int k = 1; k < rp; ++k) t += red[k * vpb + vec][e];
+                if (v * VEC + e < cols) part[(size_t)blockIdx.x * cols + v * VEC + e] = t;
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // ---- ReLU backward ----
 __global__ void relu_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ y,
                                 bf16_t* dx, size_t n) {
@@ -388,6 +436,26 @@ int launch_reduce_f32(const float* part, int nsplit, size_t elems, float* out, h
 int launch_fill_bf16(bf16_t* p, size_t n, uint32_t seed, hipStream_t st) {
     hipLaunchKernelGGL(fill_kernel, dim3(grid_for(n)), dim3(kThreads), 0, st, p, n, seed);
     return check_launch("fill");
+}
+
+int bias_grad_chunks(size_t rows, int cols) {
+    (void)cols;
+    size_t chunks = (rows + 255) / 256;  // at least 256 rows per chunk
+    const size_t cap = (size_t)kNumCU * 4;
+    if (chunks > cap) chunks = cap;
+    return (int)(chunks < 1 ? 1 : chunks);
+}
+
+int launch_bias_grad(size_t rows, int cols, const bf16_t* dy, float* db, float* part, hipStream_t st) {
+    const int chunks = bias_grad_chunks(rows, cols);
+    const size_t rpc = (rows + chunks - 1) / chunks;
+    if ((cols & 7) == 0)
+        hipLaunchKernelGGL(bias_grad_kernel<8>, dim3(chunks), dim3(256), 0, st, dy, part, rows, cols, rpc);
+    else
+        hipLaunchKernelGGL(bias_grad_kernel<1>, dim3(chunks), dim3(256), 0, st, dy, part, rows, cols, rpc);
+    int rc = check_launch("bias_grad");
+    if (rc != WAP_OK) return rc;
+    return launch_reduce_f32(part, chunks, (size_t)cols, db, st);
 }
 
 int launch_relu_bwd(const bf16_t* dy, const bf16_t* y, bf16_t* dx, size_t n, hipStream_t st) {

@@ -155,6 +155,8 @@ int launch_fill_bf16(bf16_t* p, size_t n, uint32_t seed, hipStream_t st);
 
 // memory-bound kernels
 int launch_relu_bwd(const bf16_t* dy, const bf16_t* y, bf16_t* dx, size_t n, hipStream_t st);
+int bias_grad_chunks(size_t rows, int cols);  // row chunks (= partial sums per column) of the first stage
+int launch_bias_grad(size_t rows, int cols, const bf16_t* dy, float* db, float* part, hipStream_t st);
 int launch_maxpool_fwd(int N, int H, int W, int C, int win, int stp, const bf16_t* x, bf16_t* y,
                        uint8_t* am, hipStream_t st);
 int launch_maxpool_bwd(int N, int H, int W, int C, int win, int stp, const bf16_t* dy, const uint8_t* am,

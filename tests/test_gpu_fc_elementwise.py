@@ -173,3 +173,25 @@ def test_sgd_and_cast(orc):
     wap.wap_cast_f32_bf16(n, dwd, cb)
     torch.cuda.synchronize()
     assert np.array_equal(gu.host_f64(cb), orc.round_bf16(dw.astype(np.float64)))
+
+
+@pytest.mark.parametrize("rows,cols", [(1000, 64), (37, 10), (257, 8), (5000, 4096), (200000, 64), (300001, 24), (1, 1000)])
+def test_bias_grad(orc, rows, cols):
+    """db = column sums of dy (fp32 accumulation of bf16 inputs) against the fp64 oracle; vector and scalar paths,
+    more columns than one pass covers, chunk tails, a single row; two runs are bitwise equal."""
+    import paper_1811_01532_amd as wap
+    print(f"[case] bias_grad rows={rows} cols={cols}", flush=True)
+    gb = si.normal_bf16(si.rng(420, rows % 1000 + cols), (rows, cols))
+    gd = gu.dev_bf16(gb)
+    ws = gu.workspace(wap.wap_bias_grad_workspace_bytes(rows, cols))
+    db = torch.full((cols,), float("nan"), dtype=torch.float32, device="cuda")
+    wap.wap_bias_grad(rows, cols, gd, db, ws)
+    torch.cuda.synchronize()
+    ref = orc.bias_grad(orc.bf16_bits_to_f64(gb))
+    # fp32 running sums of up to rows / chunks values each: error grows like sqrt(rows) * 2^-24 of the magnitude
+    scale = max(np.abs(ref).max(), np.sqrt(rows))
+    assert np.max(np.abs(gu.host_f64(db) - ref)) <= 1e-5 * scale
+    db2 = torch.empty_like(db)
+    wap.wap_bias_grad(rows, cols, gd, db2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(db, db2)
