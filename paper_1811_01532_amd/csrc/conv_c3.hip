@@ -31,6 +31,9 @@ struct C3Args {
     float* part;        // wgrad partial sums [gridDim.x][K][27]
     int N, H, W, K, OH, OW, pad_h, pad_w, M, relu;
     FastDiv dOHW, dOW;
+    // general filter (conv_c3_fwd_general_kernel): R x S taps, strides, reduction length R*S*3 in 16-deep steps
+    int R, S, sh, sw, Kred, ksteps;
+    FastDiv dS3;  // division by S * 3 (elements of one filter row)
 };
 
 __device__ __align__(16) unsigned int g_zero_block_c3[4] = {0u, 0u, 0u, 0u};
@@ -126,6 +129,102 @@ __global__ __launch_bounds__(NT) void conv_c3_fwd_kernel(const C3Args a) {
             }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the strip is private to this wavefront
         constexpr int VPR = K / 8;  // 16-byte vectors per pixel
+#pragma unroll
+        for (int it = 0; it < 32 * VPR / 64; ++it) {
+            const int v = it * 64 + lane;
+            const int px = v / VPR, vec = v % VPR;
+            const int mo = tile * 32 + px;
+            u32x4 val = *reinterpret_cast<const u32x4*>(st + px * OPITCH + vec * 16);
+            if (mo < a.M) *reinterpret_cast<u32x4*>(a.y + (size_t)mo * K + vec * 8) = val;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // strip reads done before the next tile overwrites it
+    }
+}
+
+// Any filter size and stride (e.g. 11x11 stride 4): the weights do not fit in registers any more (Kred = R*S*3 up
+// to a few hundred), so every work-group packs them once into MFMA fragment order in LDS,
+// [reduction step][channel block][lane][8], and its wavefronts walk 32-pixel tiles persistently; the x fragment of a
+// step is gathered element-wise exactly as above (k = r * (3 S) + j addresses element (ow*sw - pad)*3 + j of input
+// row oh*sh - pad + r).
+template <int FB>
+__global__ __launch_bounds__(NT) void conv_c3_fwd_general_kernel(const C3Args a) {
+    constexpr int K = 32 * FB;
+    constexpr int OPITCH = K * 2 + 16;
+    extern __shared__ __align__(16) unsigned char dyn[];
+    unsigned char* stage_all = dyn;                      // 4 strips of 32 * OPITCH bytes
+    u32x4* wfrag = reinterpret_cast<u32x4*>(dyn + 4 * 32 * OPITCH);  // [ksteps][FB][64]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const bf16_t* zero_src = reinterpret_cast<const bf16_t*>(g_zero_block_c3);
+
+    for (int v = threadIdx.x; v < a.ksteps * FB * 64; v += NT) {
+        const int ln = v & 63, b = (v >> 6) % FB, ks = (v >> 6) / FB;
+        unsigned short h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = ks * 16 + (ln >> 5) * 8 + e;
+            h[e] = *(k < a.Kred ? a.w + (size_t)(b * 32 + (ln & 31)) * a.Kred + k : zero_src);
+        }
+        wfrag[v] = __builtin_bit_cast(u32x4, pack8(h));
+    }
+    __syncthreads();
+
+    const int OHW = a.OH * a.OW, W3 = a.W * 3, S3 = a.S * 3;
+    const int ntiles = (a.M + 31) / 32;
+    unsigned char* st = stage_all + wave * 32 * OPITCH;
+    for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
+        const int m = tile * 32 + l32;
+        const int mm = m < a.M ? m : a.M - 1;  // tail lanes recompute the last pixel; never stored
+        const int n = (int)fdiv((uint32_t)mm, a.dOHW);
+        const int rem = mm - n * OHW;
+        const int oh = (int)fdiv((uint32_t)rem, a.dOW);
+        const int ow = rem - oh * a.OW;
+        const int ih0 = oh * a.sh - a.pad_h, iw30 = (ow * a.sw - a.pad_w) * 3;
+        const bf16_t* ximg = a.x + (size_t)n * a.H * W3;
+        f32x16 acc[FB];
+#pragma unroll
+        for (int b = 0; b < FB; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
+        for (int ks = 0; ks < a.ksteps; ++ks) {
+            unsigned short h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = ks * 16 + half * 8 + e;
+                const int r = (int)fdiv((uint32_t)k, a.dS3), j = k - r * S3;
+                const int ih = ih0 + r, iw3 = iw30 + j;
+                const bool ok = k < a.Kred && (unsigned)ih < (unsigned)a.H && (unsigned)iw3 < (unsigned)W3;
+                h[e] = *(ok ? ximg + (size_t)ih * W3 + iw3 : zero_src);
+            }
+            const bf16x8 xf = pack8(h);
+#pragma unroll
+            for (int b = 0; b < FB; ++b) {
+                const bf16x8 wf = __builtin_bit_cast(bf16x8, wfrag[(ks * FB + b) * 64 + lane]);
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[b], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < FB; ++b)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ch = b * 32 + q * 8 + half * 4;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[b][q * 4 + e];
+                if (a.bias) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += a.bias[ch + e];
+                }
+                if (a.relu) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+                }
+                *reinterpret_cast<uint2*>(st + l32 * OPITCH + ch * 2) =
+                    make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16),
+                               (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the strip is private to this wavefront
+        constexpr int VPR = K / 8;
 #pragma unroll
         for (int it = 0; it < 32 * VPR / 64; ++it) {
             const int v = it * 64 + lane;
@@ -240,9 +339,21 @@ int c3_grid(long units) {
 
 }  // namespace
 
+namespace {
+bool c3_special(const GemmGeom& g) { return g.R == 3 && g.S == 3 && g.mul_h == 1 && g.mul_w == 1; }
+size_t c3_general_smem(const GemmGeom& g) {
+    const size_t ksteps = (size_t)(g.Kred + 15) / 16;
+    return 4 * 32 * (size_t)(g.Ncols * 2 + 16) + ksteps * (g.Ncols / 32) * 64 * 16;
+}
+}  // namespace
+
 bool conv_c3_fwd_supported(const GemmGeom& g) {
-    return g.IC == 3 && g.R == 3 && g.S == 3 && g.mul_h == 1 && g.mul_w == 1 && g.div_h == 1 && g.div_w == 1 &&
-           (g.Ncols == 32 || g.Ncols == 64);
+    if (g.IC != 3 || g.div_h != 1 || g.div_w != 1 || (g.Ncols != 32 && g.Ncols != 64)) return false;
+    return c3_special(g) || c3_general_smem(g) <= 64 * 1024;
+}
+const char* conv_c3_fwd_kernel_name(const GemmGeom& g) {
+    if (c3_special(g)) return g.Ncols == 64 ? "conv_c3_fwd_kernel<2>" : "conv_c3_fwd_kernel<1>";
+    return g.Ncols == 64 ? "conv_c3_fwd_general_kernel<2>" : "conv_c3_fwd_general_kernel<1>";
 }
 
 int launch_conv_c3_fwd(const GemmGeom& g, const bf16_t* x, const bf16_t* w, const float* bias, bool relu, bf16_t* y,
@@ -268,15 +379,34 @@ int launch_conv_c3_fwd(const GemmGeom& g, const bf16_t* x, const bf16_t* w, cons
     long blocks = (((long)g.M + 31) / 32 + 3) / 4;  // 4 wavefronts per work-group, several tiles per wavefront
     if (blocks > (long)kNumCU * 8) blocks = (long)kNumCU * 8;
     const int grid = (int)blocks;
+    if (!c3_special(g)) {
+        a.R = g.R;
+        a.S = g.S;
+        a.sh = g.mul_h;
+        a.sw = g.mul_w;
+        a.Kred = g.Kred;
+        a.ksteps = (g.Kred + 15) / 16;
+        a.dS3 = make_fastdiv((uint32_t)(g.S * 3));
+        const size_t smem = c3_general_smem(g);
+        // every work-group packs the weights once: fewer, longer-lived groups than the 3x3 kernel
+        const int ggrid = grid < kNumCU * 2 ? grid : kNumCU * 2;
+        if (g.Ncols == 64) hipLaunchKernelGGL(conv_c3_fwd_general_kernel<2>, dim3(ggrid), dim3(NT), smem, st, a);
+        else hipLaunchKernelGGL(conv_c3_fwd_general_kernel<1>, dim3(ggrid), dim3(NT), smem, st, a);
+        return check_launch("conv_c3_fwd_general");
+    }
     if (g.Ncols == 64) hipLaunchKernelGGL(conv_c3_fwd_kernel<2>, dim3(grid), dim3(NT), 0, st, a);
     else hipLaunchKernelGGL(conv_c3_fwd_kernel<1>, dim3(grid), dim3(NT), 0, st, a);
     return check_launch("conv_c3_fwd");
 }
 
+// (A general-filter variant of the weight gradient was tried and dropped: with lanes indexing the columns k, the
+// element-wise gather touches a different cache line per lane, and the generic kernel, which gathers with lanes
+// indexing pixels and transposes through LDS, is faster for the 11x11 stride-4 layer.)
 bool wgrad_c3_supported(const WgradGeom& g) {
     return g.C == 3 && g.R == 3 && g.S == 3 && g.sh == 1 && g.sw == 1 && (g.K == 32 || g.K == 64) && (g.Q % 8) == 0 &&
            (long)g.N * g.P * g.Q >= 4096;
 }
+const char* wgrad_c3_kernel_name(const WgradGeom& g) { return g.K == 64 ? "wgrad_c3_kernel<2>" : "wgrad_c3_kernel<1>"; }
 
 int wgrad_c3_nsplit(const WgradGeom& g) { return c3_grid(((long)g.N * g.P * g.Q + 15) / 16); }
 

@@ -558,7 +558,7 @@ const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& p
     if (plan.cfg == 5) return "conv_wreg_kernel";
     if (plan.cfg == 6) return patch_kernel_name(g);
     if (plan.cfg == 7) return tile2d_kernel_name(g);
-    if (plan.cfg == 8) return g.Ncols == 64 ? "conv_c3_fwd_kernel<2>" : "conv_c3_fwd_kernel<1>";
+    if (plan.cfg == 8) return conv_c3_fwd_kernel_name(g);
     static const char* names[5][2][3] = {
         {{"igemm_kernel<256,256,2,4,false,0>", "", ""}, {"igemm_kernel<256,256,2,4,true,0>", "", ""}},
         {{"igemm_kernel<128,128,2,2,false,0>", "igemm_kernel<128,128,2,2,false,1>", "igemm_kernel<128,128,2,2,false,2>"},

@@ -102,9 +102,11 @@ int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf
 
 // 3-input-channel 3x3 stride-1 first layer (conv_c3.hip)
 bool conv_c3_fwd_supported(const GemmGeom& g);
+const char* conv_c3_fwd_kernel_name(const GemmGeom& g);
 int launch_conv_c3_fwd(const GemmGeom& g, const bf16_t* x, const bf16_t* w, const float* bias, bool relu, bf16_t* y,
                        hipStream_t st);
 bool wgrad_c3_supported(const WgradGeom& g);
+const char* wgrad_c3_kernel_name(const WgradGeom& g);
 int wgrad_c3_nsplit(const WgradGeom& g);
 int launch_wgrad_c3(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* part, hipStream_t st);
 

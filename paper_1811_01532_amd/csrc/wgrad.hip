@@ -365,7 +365,7 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
 namespace wap {
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan) {
     if (plan.cfg == 3) return wgrad_patch_kernel_name(g);
-    if (plan.cfg == 4) return g.K == 64 ? "wgrad_c3_kernel<2>" : "wgrad_c3_kernel<1>";
+    if (plan.cfg == 4) return wgrad_c3_kernel_name(g);
     static const char* names[3][2] = {
         {"wgrad_kernel<256,256,2,4,0>", ""},
         {"wgrad_kernel<128,128,2,2,0>", "wgrad_kernel<128,128,2,2,1>"},
