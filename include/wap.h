@@ -237,6 +237,14 @@ int wap_step_tensor(const wap_step_plan* p, int32_t index, const char** name, si
                     size_t* bytes);
 /* Enqueues one full step on `stream`: no allocation, no synchronisation. */
 int wap_step_run(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream);
+/* The same step as one HIP graph: wap_step_graph_capture records the launch list for this arena on `stream`
+ * (stream capture; nothing executes) and instantiates it, replacing any graph captured before;
+ * wap_step_graph_launch replays it.  The list holds kernel launches only (no memset or copy nodes).  At least
+ * one wap_step_run on this plan must have completed before the capture (first launches set kernel
+ * attributes, which capture does not allow): WAP_EINVAL otherwise.  The graph is bound to the arena address
+ * it was captured with and is released by wap_step_plan_destroy. */
+int wap_step_graph_capture(wap_step_plan* p, void* arena, size_t arena_bytes, void* stream);
+int wap_step_graph_launch(const wap_step_plan* p, void* stream);
 /* Algorithmic FLOPs of one step (direct-convolution count, first layer's data gradient excluded). */
 double wap_step_flops(const wap_step_plan* p);
 /* Number of operations in the launch list (an operation is one kernel, or a kernel plus its

@@ -293,6 +293,13 @@ class StepPlan:
             out.append((name.value.decode(), kern.value.decode(), fl.value, by.value))
         return out
 
+    def graph_capture(self, arena, stream):
+        """Records the step for this arena as one HIP graph (after at least one eager run)."""
+        _check(lib().wap_step_graph_capture(self._p, _ptr(arena), ctypes.c_size_t(_nbytes(arena)), _stream(stream)))
+
+    def graph_launch(self, stream):
+        _check(lib().wap_step_graph_launch(self._p, _stream(stream)))
+
     def time(self, arena, steps=1, stream=None, op_mask=None, with_prologue=False):
         """`steps` steps with events around every operation (or only those whose op_mask entry is true):
         (main-kernel us, epilogue-kernel us) lists, plus the weight-repacking-kernel us list on request."""

@@ -80,6 +80,10 @@ struct wap_step_plan {
     size_t w32_off = 0, dw_off = 0, wb_off = 0;
     mutable std::vector<hipEvent_t> events;  // cached by wap_step_time
     PackJobs packjobs = {};                  // every weight repacking of the step, run as one kernel
+    mutable bool ran_once = false;           // an eager step has completed its launches (kernel attributes are set)
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t graph_exec = nullptr;
+    void* graph_arena = nullptr;
 
     size_t add(const std::string& name, size_t bytes) {
         size_t off = arena;
@@ -431,6 +435,8 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
 void wap_step_plan_destroy(wap_step_plan* p) {
     if (!p) return;
     for (hipEvent_t e : p->events) (void)hipEventDestroy(e);
+    if (p->graph_exec) (void)hipGraphExecDestroy(p->graph_exec);
+    if (p->graph) (void)hipGraphDestroy(p->graph);
     delete p;
 }
 
@@ -469,6 +475,49 @@ int wap_step_run(const wap_step_plan* p, void* arena, size_t arena_bytes, void* 
         rc = run_op(p, op, base, (hipStream_t)stream);
         if (rc != WAP_OK) return rc;
     }
+    p->ran_once = true;
+    return WAP_OK;
+}
+
+int wap_step_graph_capture(wap_step_plan* p, void* arena, size_t arena_bytes, void* stream) {
+    int rc = check_arena(p, arena, arena_bytes);
+    if (rc != WAP_OK) return rc;
+    if (!p->ran_once) return set_error(WAP_EINVAL, "step graph: run one eager step (wap_step_run) before capturing");
+    if (!stream) return set_error(WAP_EINVAL, "step graph: capture needs an explicit (non-default) stream");
+    hipStream_t st = (hipStream_t)stream;
+    if (p->graph_exec) { (void)hipGraphExecDestroy(p->graph_exec); p->graph_exec = nullptr; }
+    if (p->graph) { (void)hipGraphDestroy(p->graph); p->graph = nullptr; }
+    hipError_t e = hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) return set_error(WAP_EHIP, "hipStreamBeginCapture: %s", hipGetErrorString(e));
+    unsigned char* base = (unsigned char*)arena;
+    for (const Op& op : p->ops) {
+        rc = run_op(p, op, base, st);
+        if (rc != WAP_OK) break;
+    }
+    hipGraph_t g = nullptr;
+    e = hipStreamEndCapture(st, &g);
+    if (rc != WAP_OK) {
+        if (g) (void)hipGraphDestroy(g);
+        return rc;
+    }
+    if (e != hipSuccess || !g) return set_error(WAP_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
+    hipGraphExec_t ge = nullptr;
+    e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        (void)hipGraphDestroy(g);
+        return set_error(WAP_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e));
+    }
+    p->graph = g;
+    p->graph_exec = ge;
+    p->graph_arena = arena;
+    return WAP_OK;
+}
+
+int wap_step_graph_launch(const wap_step_plan* p, void* stream) {
+    if (!p) return set_error(WAP_EINVAL, "step graph: NULL plan");
+    if (!p->graph_exec) return set_error(WAP_EINVAL, "step graph: nothing captured");
+    hipError_t e = hipGraphLaunch(p->graph_exec, (hipStream_t)stream);
+    if (e != hipSuccess) return set_error(WAP_EHIP, "hipGraphLaunch: %s", hipGetErrorString(e));
     return WAP_OK;
 }
 

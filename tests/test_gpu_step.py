@@ -194,3 +194,43 @@ def test_step_without_kept_gradients_is_bitwise_the_same(orc):
     assert torch.equal(res[0][1], res[1][1])
     assert res[0][2] == res[1][2]
     assert np.isfinite(res[0][2])
+
+
+@pytest.mark.parametrize("net,B,image", [("vgg16", 2, 64), ("alexnet", 3, 67)])
+def test_step_graph_replays_match_eager_steps(orc, net, B, image):
+    """The step captured as one HIP graph: every replay (several, with the program's own eager work and
+    synchronisations in between) leaves the whole arena bitwise equal to the eager step from the same state;
+    capturing before any eager run is rejected."""
+    import paper_1811_01532_amd as wap
+    plan, ar, *_ = _setup(net, B, image, 0, 520)
+    print(f"[case] step graph {net} B={B} image={image}", flush=True)
+    side = torch.cuda.Stream()
+    with pytest.raises(wap.WapError):
+        plan.graph_capture(ar.buf, side)
+    start = ar.buf.clone()
+    # eager reference: three consecutive steps from the initial state
+    refs = []
+    for _ in range(3):
+        plan.run(ar.buf)
+        torch.cuda.synchronize()
+        refs.append(ar.buf.clone())
+    ws_off, ws_nb = ar.t["workspace"]
+
+    def same(a, b):   # the workspace holds dead partial sums of whichever split reduction ran last: compare the rest
+        return torch.equal(a[:ws_off], b[:ws_off]) and torch.equal(a[ws_off + ws_nb:], b[ws_off + ws_nb:])
+
+    ar.buf.copy_(start)
+    torch.cuda.synchronize()
+    plan.graph_capture(ar.buf, side)          # records only: the arena must be untouched
+    torch.cuda.synchronize()
+    assert torch.equal(ar.buf, start)
+    for rep in range(3):
+        ar.buf.copy_(start)
+        scratch = torch.relu(torch.randn(1 << 16, device="cuda")).sum()   # unrelated eager work between replays
+        torch.cuda.synchronize()
+        side.wait_stream(torch.cuda.current_stream())
+        for k in range(3):
+            plan.graph_launch(side)
+            side.synchronize()
+            assert same(ar.buf, refs[k]), f"replay round {rep}, step {k} differs from the eager step"
+        assert np.isfinite(float(scratch))
