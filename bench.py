@@ -298,7 +298,7 @@ def main():
         # ---- step-level utilisation versus per-GPU minibatch, both networks ----
         table = []
         for tnet in ("alexnet", "vgg16"):
-            for b in (8, 16, 32, 64, 128, 256):
+            for b in (8, 16, 32, 64, 128, 256) + ((512,) if tnet == "alexnet" else ()):
                 p = wap.StepPlan(tnet, b, lr=LR, image=image)
                 bb = _arena(p, torch)
                 init_step(p, bb, tnet, b, image, torch, wap, "device")
@@ -377,6 +377,24 @@ def main():
                       "note": "t_c measured on this GPU at minibatch B/d (wap_profile_layer); t_s analytic (ring all-reduce "
                               "over one xGMI link, fp32 gradients); no multi-GPU run is involved",
                       "decisions": wau_rows}
+        # ---- the FC head as model-parallel shards (the hybrid direction the paper's Section 2 leaves open): one GPU's
+        # share is a slice of out_features / d output neurons at the FULL minibatch, through the same kernels ----
+        shard_rows = []
+        shard_mbs = sorted({B, 256})
+        for (name, n_in, n_out, relu) in si.NETS[net][1]:
+            for d in (1, 2, 4, 8):
+                n_sh = (n_out + d - 1) // d
+                desc = wap.fc_desc(1, n_in, n_sh, relu)
+                scratch = torch.empty(wap.wap_profile_scratch_bytes(1, desc, shard_mbs) + 256, dtype=torch.uint8, device="cuda")
+                for r in wap.wap_profile_layer(1, desc, shard_mbs, 2, 7, scratch):
+                    shard_rows.append({"layer": name, "d": d, "out_features": n_sh, "minibatch": r.minibatch,
+                                       "pass": ("fwd", "dgrad", "wgrad")[r.pass_], "us": round(r.time_us_median, 2),
+                                       "tflops": round(r.tflops, 2), "frac_peak": round(r.frac_of_bf16_peak, 4),
+                                       "gbs": round(r.gbytes_per_s, 1), "bound": ("mfma", "hbm")[r.bound]})
+                del scratch
+                torch.cuda.empty_cache()
+        out["fc_shards"] = {"note": "FC layers of the headline network cut into d slices of output neurons, full minibatch per "
+                                    "slice (model-parallel share of one GPU); dgrad is the slice's partial dx", "rows": shard_rows}
         md.append("| net | minibatch | ms/step | TFLOP/s | frac of bf16 peak | images/s |\n|---|---|---|---|---|---|")
         for r in table:
             md.append(f"| {r['net']} | {r['minibatch']} | {r['ms_per_step']} | {r['tflops']} | "
@@ -385,6 +403,11 @@ def main():
         for r in wau_rows:
             md.append(f"| {r['net']} | {r['global_minibatch']} | "
                       + ", ".join(f"d={d}: {t}" for d, t in r["t_estimate_ms"].items()) + f" | {r['best_d']} |")
+        md.append("\n| FC layer | d | out features per shard | minibatch | pass | us | TFLOP/s | GB/s | side of ridge |\n"
+                  "|---|---|---|---|---|---|---|---|---|")
+        for r in shard_rows:
+            md.append(f"| {r['layer']} | {r['d']} | {r['out_features']} | {r['minibatch']} | {r['pass']} | {r['us']} | "
+                      f"{r['tflops']} | {r['gbs']} | {r['bound']} |")
         md.append("\n| layer | pass | minibatch | us | TFLOP/s | frac of peak | GB/s | side of ridge |\n|---|---|---|---|---|---|---|---|")
         for r in layers:
             md.append(f"| {r['layer']} | {r['pass']} | {r['minibatch']} | {r['us']} | {r['tflops']} | "

@@ -18,6 +18,9 @@ FC_CASES = [
     ("b512_128_264_big_tiles", 512, 128, 264, (0, 0, -1)),
     ("b8_2048_512_split", 8, 2048, 512, (-1, -1, -1)),
     ("b33_vec_general", 33, 72, 136, (-1, -1, -1)),
+    # model-parallel shards of the VGG-16 head: out_features / 8 at the full minibatch
+    ("fc8_shard_125", 64, 4096, 125, (-1, -1, -1)),
+    ("fc6_shard_512", 64, 25088, 512, (-1, -1, -1)),
 ]
 
 
