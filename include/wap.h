@@ -117,6 +117,26 @@ int wap_conv2d_bwd_data_relu(const wap_conv_desc* d, const void* dy, const void*
 int wap_conv2d_bwd_weight(const wap_conv_desc* d, const void* x, const void* dy, float* dw,
                           void* ws, size_t ws_bytes, void* stream);
 
+/* Backward passes of a convolution whose (ReLU) output went through a 2x2 / stride-2 max-pool (the
+ * conv -> ReLU -> pool chain of a VGG block; the pool's backward is an auxiliary node between two primary
+ * nodes, Section 3.2.2).  Instead of the full-size dy the caller passes g_pool, the bf16 gradient w.r.t. the
+ * POOLED output [N][P/2][Q/2][K], and argmax (uint8, same shape, r*2+s as written by wap_maxpool_fwd or
+ * wap_conv2d_fwd_pool2x2); the operand the product sees is
+ *     dy[n,p,q,k] = (argmax[n,p/2,q/2,k] == (p%2)*2 + q%2) ? g_pool[n,p/2,q/2,k] : 0,
+ * i.e. wap_maxpool_bwd(win 2, stride 2, no ReLU mask) followed by wap_conv2d_bwd_data(_relu) /
+ * wap_conv2d_bwd_weight, bit for bit.  P and Q must be even.  The ReLU derivative of the pooled layer
+ * itself belongs in g_pool (mask it with the pooled activation > 0: the routed value is the window's
+ * maximum).  Where the kernel's loader can do the routing (wap_conv2d_bwd_pool2x2_fused reports 1 for the
+ * pass) the full-size dy never exists and dy_full may be NULL; otherwise dy_full (bf16 [N][P][Q][K]
+ * device scratch) is required and the two kernels run back to back.  x_act of the data gradient is
+ * optional (NULL: no ReLU derivative of the layer below). */
+int wap_conv2d_bwd_data_pool2x2(const wap_conv_desc* d, const void* g_pool, const uint8_t* argmax, const void* w,
+                                const void* x_act, void* dx, void* dy_full, void* ws, size_t ws_bytes, void* stream);
+int wap_conv2d_bwd_weight_pool2x2(const wap_conv_desc* d, const void* x, const void* g_pool, const uint8_t* argmax,
+                                  float* dw, void* dy_full, void* ws, size_t ws_bytes, void* stream);
+/* pass: WAP_PASS_BWD_DATA or WAP_PASS_BWD_WEIGHT */
+int wap_conv2d_bwd_pool2x2_fused(const wap_conv_desc* d, int pass, int32_t* fused_out);
+
 /* ---- fully connected (primary node, Section 3.2.2) ---- */
 int wap_fc_workspace_bytes(const wap_fc_desc* d, int pass, size_t* bytes_out);
 

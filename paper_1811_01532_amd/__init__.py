@@ -155,6 +155,23 @@ def wap_conv2d_bwd_weight(desc, x, dy, dw, ws=None, stream=None):
                                        ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
 
 
+def wap_conv2d_bwd_data_pool2x2(desc, g_pool, argmax, w, x_act, dx, dy_full=None, ws=None, stream=None):
+    _check(lib().wap_conv2d_bwd_data_pool2x2(ctypes.byref(desc), _ptr(g_pool), _ptr(argmax), _ptr(w), _ptr(x_act),
+                                             _ptr(dx), _ptr(dy_full), _ptr(ws), ctypes.c_size_t(_nbytes(ws)),
+                                             _stream(stream)))
+
+
+def wap_conv2d_bwd_weight_pool2x2(desc, x, g_pool, argmax, dw, dy_full=None, ws=None, stream=None):
+    _check(lib().wap_conv2d_bwd_weight_pool2x2(ctypes.byref(desc), _ptr(x), _ptr(g_pool), _ptr(argmax), _ptr(dw),
+                                               _ptr(dy_full), _ptr(ws), ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
+
+
+def wap_conv2d_bwd_pool2x2_fused(desc, pass_):
+    out = ctypes.c_int32(0)
+    _check(lib().wap_conv2d_bwd_pool2x2_fused(ctypes.byref(desc), int(pass_), ctypes.byref(out)))
+    return bool(out.value)
+
+
 def wap_fc_fwd(desc, x, Wt, bias, y, ws=None, stream=None):
     _check(lib().wap_fc_fwd(ctypes.byref(desc), _ptr(x), _ptr(Wt), _ptr(bias), _ptr(y), _ptr(ws),
                             ctypes.c_size_t(_nbytes(ws)), _stream(stream)))

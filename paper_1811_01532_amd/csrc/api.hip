@@ -248,6 +248,66 @@ int wap_conv2d_bwd_weight(const wap_conv_desc* d, const void* x, const void* dy,
     return launch_wgrad(g, p, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, (hipStream_t)stream);
 }
 
+static int check_pool2x2_bwd(const wap_conv_desc* d, const void* g_pool, const uint8_t* argmax) {
+    WAP_TRY(validate_conv(d));
+    WAP_TRY(check_ptr(g_pool, "g_pool"));
+    WAP_TRY(check_ptr(argmax, "argmax"));
+    const int P = out_dim(d->H, d->pad_h, d->R, d->stride_h), Q = out_dim(d->W, d->pad_w, d->S, d->stride_w);
+    if ((P & 1) || (Q & 1)) return set_error(WAP_EINVAL, "bwd_pool2x2: output size %dx%d is not even", P, Q);
+    return WAP_OK;
+}
+
+int wap_conv2d_bwd_pool2x2_fused(const wap_conv_desc* d, int pass, int32_t* fused_out) {
+    WAP_TRY(validate_conv(d));
+    if (!fused_out) return set_error(WAP_EINVAL, "bwd_pool2x2_fused: NULL argument");
+    if (pass == WAP_PASS_BWD_DATA) {
+        GemmGeom g = geom_conv_dgrad(*d);
+        *fused_out = fwd_like_fuses_unpool(g, plan_fwd_like(g, true)) ? 1 : 0;
+    } else if (pass == WAP_PASS_BWD_WEIGHT) {
+        WgradGeom g = geom_conv_wgrad(*d);
+        *fused_out = wgrad_fuses_unpool(g, plan_wgrad(g)) ? 1 : 0;
+    } else {
+        return set_error(WAP_EINVAL, "bwd_pool2x2_fused: pass %d is not a backward pass", pass);
+    }
+    return WAP_OK;
+}
+
+int wap_conv2d_bwd_data_pool2x2(const wap_conv_desc* d, const void* g_pool, const uint8_t* argmax, const void* w,
+                                const void* x_act, void* dx, void* dy_full, void* ws, size_t ws_bytes, void* stream) {
+    WAP_TRY(check_pool2x2_bwd(d, g_pool, argmax));
+    WAP_TRY(check_ptr(w, "w"));
+    WAP_TRY(check_ptr(dx, "dx"));
+    if (x_act && !aligned16(x_act)) return set_error(WAP_EINVAL, "x_act is not 16-byte aligned");
+    GemmGeom g = geom_conv_dgrad(*d);
+    GemmPlan p = plan_fwd_like(g, true);
+    WAP_TRY(check_ws(p.ws_bytes, ws, ws_bytes));
+    if (fwd_like_fuses_unpool(g, p))
+        return launch_fwd_like(g, true, p, (const bf16_t*)g_pool, (const bf16_t*)w, nullptr, false, (bf16_t*)dx, ws,
+                               (hipStream_t)stream, nullptr, (const bf16_t*)x_act, nullptr, nullptr, nullptr, nullptr,
+                               argmax);
+    WAP_TRY(check_ptr(dy_full, "dy_full (this shape is not fused)"));
+    WAP_TRY(launch_maxpool_bwd(d->N, g.IH, g.IW, d->K, 2, 2, (const bf16_t*)g_pool, argmax, nullptr, (bf16_t*)dy_full,
+                               (hipStream_t)stream));
+    return launch_fwd_like(g, true, p, (const bf16_t*)dy_full, (const bf16_t*)w, nullptr, false, (bf16_t*)dx, ws,
+                           (hipStream_t)stream, nullptr, (const bf16_t*)x_act);
+}
+
+int wap_conv2d_bwd_weight_pool2x2(const wap_conv_desc* d, const void* x, const void* g_pool, const uint8_t* argmax,
+                                  float* dw, void* dy_full, void* ws, size_t ws_bytes, void* stream) {
+    WAP_TRY(check_pool2x2_bwd(d, g_pool, argmax));
+    WAP_TRY(check_ptr(x, "x"));
+    WAP_TRY(check_ptr(dw, "dw"));
+    WgradGeom g = geom_conv_wgrad(*d);
+    WgradPlan p = plan_wgrad(g);
+    WAP_TRY(check_ws(p.ws_bytes, ws, ws_bytes));
+    if (wgrad_fuses_unpool(g, p))
+        return launch_wgrad(g, p, (const bf16_t*)x, (const bf16_t*)g_pool, dw, ws, (hipStream_t)stream, nullptr, argmax);
+    WAP_TRY(check_ptr(dy_full, "dy_full (this shape is not fused)"));
+    WAP_TRY(launch_maxpool_bwd(d->N, g.P, g.Q, d->K, 2, 2, (const bf16_t*)g_pool, argmax, nullptr, (bf16_t*)dy_full,
+                               (hipStream_t)stream));
+    return launch_wgrad(g, p, (const bf16_t*)x, (const bf16_t*)dy_full, dw, ws, (hipStream_t)stream);
+}
+
 int wap_fc_workspace_bytes(const wap_fc_desc* d, int pass, size_t* bytes_out) {
     WAP_TRY(validate_fc(d));
     if (!bytes_out) return set_error(WAP_EINVAL, "bytes_out is NULL");

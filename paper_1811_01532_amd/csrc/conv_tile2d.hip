@@ -14,6 +14,9 @@
 //     (LDS and registers are sized for that): while one group waits for its patch or drains its
 //     epilogue the others keep the matrix cores busy, which suits layers whose 64 input channels give
 //     each group a single slice and nothing of its own to overlap with.
+// UP variant (data gradient of a layer followed by a 2x2 / stride-2 max-pool): the input operand arrives as
+// the gradient of the POOLED output plus the pool's argmax; the patch loader routes each window's value to
+// the pixel its argmax names, so the max-pool backward costs no pass over the full-size gradient.
 // Serves the "primary" convolution nodes of Section 3.2.2 (forward and backward halves of t_c, Eq. 1).
 #include "wap_internal.h"
 
@@ -31,6 +34,7 @@ struct TArgs {
     const bf16_t* Wp;  // packed weights
     const float* bias;
     const bf16_t* mask;  // optional: out = mask > 0 ? out : 0
+    const uint8_t* up_am;  // UP: argmax (r * 2 + s) per pooling window; A is then N x IH/2 x IW/2 x IC
     bf16_t* out;         // may be NULL when only the pooled output is wanted
     bf16_t* pool_y;      // optional (2-D 256-pixel tiles only): 2x2 / stride-2 max-pool of the output tile ...
     uint8_t* pool_am;    // ... and the position r*2+s of the first maximum of every window
@@ -42,6 +46,8 @@ struct TArgs {
     unsigned a_bytes, w_bytes;
     FastDiv dTimg, dTx, dPWp;
     FastDiv dOHW, dOW, dPHW;  // flat tiles
+    int UW, units;            // UP, 2-D tiles: pooling windows per patch row, windows per patch
+    FastDiv dUW;
 };
 
 __device__ __forceinline__ int xcd_remap(int bid, int total) {
@@ -65,11 +71,24 @@ __device__ __forceinline__ u32x4 relu_mask8(u32x4 v, u32x4 mk) {
     return v;
 }
 
+// keeps the bf16 lanes of the pooled gradient v whose window's argmax byte equals this pixel's position code
+__device__ __forceinline__ u32x4 unpool_select8(u32x4 v, u32x2 am, unsigned code) {
+    const unsigned c4 = code * 0x01010101u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const unsigned x = ((k < 2 ? am[0] : am[1]) >> ((k & 1) * 16)) ^ c4;  // a zero byte where argmax == code
+        const unsigned lo = (x & 0xffu) == 0u ? 0xffffu : 0u;
+        const unsigned hi = (x & 0xff00u) == 0u ? 0xffff0000u : 0u;
+        v[k] &= (lo | hi);
+    }
+    return v;
+}
+
 // FN: 32-channel blocks per wavefront; TW: tile width in pixels; FM: 32-pixel fragments per wavefront;
 // PG: wavefronts along the pixels (4 / PG along the channels).  Tile = 32*FM*PG pixels x 32*FN*(4/PG) channels.
 // TW = 0: flat tiles, 32*FM*PG consecutive output pixels in raster order (they may straddle rows and images;
-// the patch is then a run of the zero-padded image in raster order, as in conv_patch.hip).
-template <int FN, int TW, int FM, int PG>
+// the patch is then a run of the zero-padded image in raster order, as in conv_patch.hip).  UP: pooled input operand.
+template <int FN, int TW, int FM, int PG, bool UP>
 __global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel(const TArgs a) {
     constexpr bool FLAT = (TW == 0);
     constexpr int BM = 32 * FM * PG;
@@ -113,11 +132,18 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel
     const __amdgpu_buffer_rsrc_t rsrcW =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a.Wp), 0, (int)a.w_bytes, 0x00020000);
     constexpr unsigned OOB = 0x80000000u;  // the activation tensor is below 2 GiB (checked on the host)
+    const __amdgpu_buffer_rsrc_t rsrcM =  // UP: one argmax byte per pooled element, half the bytes of the pooled tensor
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(UP ? a.up_am : nullptr), 0, UP ? (int)(a.a_bytes / 2) : 0, 0x00020000);
+    const int IH2 = g.IH >> 1, IW2 = g.IW >> 1;
 
-    // ---- patch vectors of this thread: byte offset of (padded pixel, 8-channel vector) or OOB ----
-    unsigned pvoff[PV];
+    // ---- patch vectors of this thread: byte offset of (padded pixel, 8-channel vector) or OOB.  UP: the offset is
+    // that of the pixel's pooling window in the pooled tensor (the argmax byte sits at half of it), and pvcode holds
+    // the pixel's position (ih % 2) * 2 + iw % 2 inside the window, 2 bits per vector ----
+    constexpr bool UNITS = UP && !FLAT;  // 2-D tiles: a thread fetches whole pooling windows instead (below)
+    unsigned pvoff[UNITS ? 1 : PV];
+    unsigned pvcode = 0;
 #pragma unroll
-    for (int i = 0; i < PV; ++i) {
+    for (int i = 0; i < (UNITS ? 0 : PV); ++i) {
         int v = tid + i * NT;
         int q = v >> 3;
         unsigned off = OOB;
@@ -128,17 +154,59 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel
                 int rem = p - n * PHW;
                 int vh = (int)fdiv((uint32_t)rem, a.dPWp);
                 int ih = vh - g.pad_h, iw = rem - vh * a.PWp - g.pad_w;
-                if (n * OHW < g.M && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW)
-                    off = (unsigned)(((n * g.IH + ih) * g.IW + iw) * g.IC + (v & 7) * 8) * 2u;
+                if (n * OHW < g.M && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW) {
+                    if (UP) {
+                        off = (unsigned)(((n * IH2 + (ih >> 1)) * IW2 + (iw >> 1)) * g.IC + (v & 7) * 8) * 2u;
+                        pvcode |= (unsigned)(((ih & 1) << 1) | (iw & 1)) << (2 * i);
+                    } else {
+                        off = (unsigned)(((n * g.IH + ih) * g.IW + iw) * g.IC + (v & 7) * 8) * 2u;
+                    }
+                }
             } else {
                 int py = (int)fdiv((uint32_t)q, a.dPWp);
                 int px = q - py * a.PWp;
                 int ih = oh0 - g.pad_h + py, iw = ow0 - g.pad_w + px;
-                if ((unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW)
-                    off = (unsigned)(((img * g.IH + ih) * g.IW + iw) * g.IC + (v & 7) * 8) * 2u;
+                if ((unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW) {
+                    if (UP) {
+                        off = (unsigned)(((img * IH2 + (ih >> 1)) * IW2 + (iw >> 1)) * g.IC + (v & 7) * 8) * 2u;
+                        pvcode |= (unsigned)(((ih & 1) << 1) | (iw & 1)) << (2 * i);
+                    } else {
+                        off = (unsigned)(((img * g.IH + ih) * g.IW + iw) * g.IC + (v & 7) * 8) * 2u;
+                    }
+                }
             }
         }
         pvoff[i] = off;
+    }
+
+    // ---- UP, 2-D tiles: window `unit` = thread index / 8 (+ 32 per round) of the (UH x UW) windows that touch the
+    // patch; one 16-byte load of the pooled gradient and one 8-byte load of the argmax serve its four pixels.
+    // uq0 = patch row of the window's top-left pixel (it may lie one row / column outside the patch), uval = which of
+    // the four pixels are inside the patch, 4 bits per window ----
+    constexpr int UPV = 4;
+    unsigned uoff[UNITS ? UPV : 1];
+    int uq0[UNITS ? UPV : 1];
+    unsigned uval = 0;
+    if (UNITS) {
+        const int ihf = oh0 - g.pad_h, iwf = ow0 - g.pad_w;  // image coordinates of patch pixel (0, 0)
+        const int wy0 = ihf >> 1, wx0 = iwf >> 1;            // its window (floor division also below zero)
+        const int PHt = TH + g.R - 1;
+#pragma unroll
+        for (int i = 0; i < UPV; ++i) {
+            const int unit = (tid >> 3) + i * (NT / 8);
+            const int uy = (int)fdiv((uint32_t)unit, a.dUW), ux = unit - uy * a.UW;
+            const int wy = wy0 + uy, wx = wx0 + ux;
+            const int py = 2 * wy - ihf, px = 2 * wx - iwf;
+            unsigned off = OOB;
+            if (unit < a.units && (unsigned)wy < (unsigned)IH2 && (unsigned)wx < (unsigned)IW2)
+                off = (unsigned)(((img * IH2 + wy) * IW2 + wx) * g.IC + (tid & 7) * 8) * 2u;
+            uoff[i] = off;
+            uq0[i] = py * a.PWp + px;
+            if (unit < a.units) {
+                const unsigned vy0 = py >= 0, vy1 = py + 1 < PHt, vx0 = px >= 0, vx1 = px + 1 < a.PWp;
+                uval |= ((vy0 & vx0) | ((vy0 & vx1) << 1) | ((vy1 & vx0) << 2) | ((vy1 & vx1) << 3)) << (4 * i);
+            }
+        }
     }
 
     // ---- fragment rows of this lane: fragment j holds tile pixels (pg * 4 + j) * 32 .. + 31 in raster order ----
@@ -184,11 +252,35 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel
     load_w(0, 0, wA);
 
     for (int cs = 0; cs < ncs; ++cs) {
-        {
+        if (UNITS) {
+            u32x4 rp[UPV];
+            u32x2 ra[UPV];  // the out-of-range offset halves to one that is still past the (half as long) argmax tensor
+            const unsigned coff = (unsigned)(cs * BK) * 2u;
+#pragma unroll
+            for (int i = 0; i < UPV; ++i) {
+                rp[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, uoff[i] + coff, 0, 0);
+                ra[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrcM, (uoff[i] + coff) >> 1, 0, 0);
+            }
+            if (cs > 0) __syncthreads();  // every wavefront has finished reading the previous slice's patch
+#pragma unroll
+            for (int i = 0; i < UPV; ++i)
+#pragma unroll
+                for (int pos = 0; pos < 4; ++pos)
+                    if ((uval >> (4 * i + pos)) & 1u)
+                        *reinterpret_cast<u32x4*>(smem + (uq0[i] + (pos >> 1) * a.PWp + (pos & 1)) * PITCH + (tid & 7) * 16) =
+                            unpool_select8(rp[i], ra[i], (unsigned)pos);
+        } else {
             u32x4 rp[PV];
             const unsigned coff = (unsigned)(cs * BK) * 2u;
 #pragma unroll
             for (int i = 0; i < PV; ++i) rp[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, pvoff[i] + coff, 0, 0);
+            if (UP) {
+                u32x2 ra[PV];  // the out-of-range offset halves to one that is still past the (half as long) argmax tensor
+#pragma unroll
+                for (int i = 0; i < PV; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b64(rsrcM, (pvoff[i] + coff) >> 1, 0, 0);
+#pragma unroll
+                for (int i = 0; i < PV; ++i) rp[i] = unpool_select8(rp[i], ra[i], (pvcode >> (2 * i)) & 3u);
+            }
             if (cs > 0) __syncthreads();  // every wavefront has finished reading the previous slice's patch
 #pragma unroll
             for (int i = 0; i < PV; ++i) {
@@ -341,9 +433,9 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel
     }
 }
 
-template <int FN, int TW, int FM, int PG>
-int launch_tile2d_t(const TArgs& ta, hipStream_t st) {
-    auto kfn = conv_tile2d_kernel<FN, TW, FM, PG>;
+template <int FN, int TW, int FM, int PG, bool UP>
+int launch_tile2d_u(const TArgs& ta, hipStream_t st) {
+    auto kfn = conv_tile2d_kernel<FN, TW, FM, PG, UP>;
     constexpr size_t smem = (size_t)(TW == 0 ? MAX_PATCH_FLAT : MAX_PATCH) * PITCH;
     static bool attr_done = false;
     if (!attr_done) {
@@ -354,6 +446,10 @@ int launch_tile2d_t(const TArgs& ta, hipStream_t st) {
     }
     hipLaunchKernelGGL(kfn, dim3(ta.tiles_m * ta.tiles_n), dim3(NT), smem, st, ta);
     return check_launch("conv_tile2d");
+}
+template <int FN, int TW, int FM, int PG>
+int launch_tile2d_t(const TArgs& ta, hipStream_t st) {
+    return ta.up_am ? launch_tile2d_u<FN, TW, FM, PG, true>(ta, st) : launch_tile2d_u<FN, TW, FM, PG, false>(ta, st);
 }
 
 }  // namespace
@@ -418,14 +514,27 @@ bool tile2d_preferred(const GemmGeom& g) {
     return (long)((g.M + 223) / 224) * (g.Ncols / 128) >= kNumCU * 3 / 4;
 }
 
-const char* tile2d_kernel_name(const GemmGeom& g) {
+const char* tile2d_kernel_name(const GemmGeom& g, bool unpool) {
     const TileCfg c = tile_cfg(g);
-    if (c.variant == 1) return "conv_tile2d_kernel<1,28,7,1>";
-    if (c.variant == 2) return "conv_tile2d_kernel<1,0,7,1>";
-    static const char* names[2][3] = {
-        {"conv_tile2d_kernel<1,32,4,2>", "conv_tile2d_kernel<1,16,4,2>", "conv_tile2d_kernel<1,8,4,2>"},
-        {"conv_tile2d_kernel<2,32,4,2>", "conv_tile2d_kernel<2,16,4,2>", "conv_tile2d_kernel<2,8,4,2>"}};
-    return names[c.fn == 2 ? 1 : 0][c.tw == 32 ? 0 : c.tw == 16 ? 1 : 2];
+    const int u = unpool ? 1 : 0;
+    static const char* n1[2] = {"conv_tile2d_kernel<1,28,7,1,false>", "conv_tile2d_kernel<1,28,7,1,true>"};
+    static const char* n2[2] = {"conv_tile2d_kernel<1,0,7,1,false>", "conv_tile2d_kernel<1,0,7,1,true>"};
+    if (c.variant == 1) return n1[u];
+    if (c.variant == 2) return n2[u];
+    static const char* names[2][2][3] = {
+        {{"conv_tile2d_kernel<1,32,4,2,false>", "conv_tile2d_kernel<1,16,4,2,false>", "conv_tile2d_kernel<1,8,4,2,false>"},
+         {"conv_tile2d_kernel<2,32,4,2,false>", "conv_tile2d_kernel<2,16,4,2,false>", "conv_tile2d_kernel<2,8,4,2,false>"}},
+        {{"conv_tile2d_kernel<1,32,4,2,true>", "conv_tile2d_kernel<1,16,4,2,true>", "conv_tile2d_kernel<1,8,4,2,true>"},
+         {"conv_tile2d_kernel<2,32,4,2,true>", "conv_tile2d_kernel<2,16,4,2,true>", "conv_tile2d_kernel<2,8,4,2,true>"}}};
+    return names[u][c.fn == 2 ? 1 : 0][c.tw == 32 ? 0 : c.tw == 16 ? 1 : 2];
+}
+
+// can the patch loader take the input operand pooled (2x2 / stride 2, whole windows) plus the argmax?
+bool tile2d_fuses_unpool(const GemmGeom& g) {
+    if (!tile2d_supported(g) || (g.IH % 2) != 0 || (g.IW % 2) != 0) return false;
+    const TileCfg c = tile_cfg(g);
+    if (c.variant == 2) return true;
+    return ((c.th + g.R - 1) / 2 + 1) * ((c.tw + g.S - 1) / 2 + 1) <= 4 * (NT / 8);  // windows per patch: 4 per 8 threads
 }
 
 // can the epilogue also emit the 2x2 / stride-2 max-pool of the output?
@@ -435,9 +544,12 @@ bool tile2d_fuses_pool(const GemmGeom& g) {
 }
 
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am) {
+                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am) {
     TArgs ta = {};
     ta.mask = mask;
+    if (unpool_am && !tile2d_fuses_unpool(g))
+        return set_error(WAP_EINVAL, "internal: fused max-pool backward not available for this shape");
+    ta.up_am = unpool_am;
     if ((pool_y || pool_am) && !(pool_y && pool_am && tile2d_fuses_pool(g)))
         return set_error(WAP_EINVAL, "internal: fused pooling not available for this shape");
     if (!out && !pool_y) return set_error(WAP_EINVAL, "internal: no output");
@@ -468,9 +580,13 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
         ta.tiles_m = ta.tiles_img * (g.M / (g.OH * g.OW));
         ta.PWp = c.tw + g.S - 1;
         ta.patch_len = (c.th + g.R - 1) * ta.PWp;
+        // windows that can touch the patch: its first pixel may be the second of its window
+        ta.UW = (c.tw + g.S - 1) / 2 + 1;
+        ta.units = ((c.th + g.R - 1) / 2 + 1) * ta.UW;
+        ta.dUW = make_fastdiv((uint32_t)ta.UW);
     }
     ta.relu = relu ? 1 : 0;
-    ta.a_bytes = (unsigned)((size_t)(g.M / (g.OH * g.OW)) * g.IH * g.IW * g.IC * 2);
+    ta.a_bytes = (unsigned)((size_t)(g.M / (g.OH * g.OW)) * g.IH * g.IW * g.IC * 2 / (unpool_am ? 4 : 1));
     ta.w_bytes = (unsigned)wreg_wt_bytes(g);
     ta.dTimg = make_fastdiv((uint32_t)ta.tiles_img);
     ta.dTx = make_fastdiv((uint32_t)ta.tiles_x);

@@ -454,9 +454,11 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
                     hipStream_t st, hipEvent_t ev_mid, const bf16_t* relu_mask, hipEvent_t ev_packed,
-                    const void* prepacked, bf16_t* pool_y, uint8_t* pool_am) {
+                    const void* prepacked, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am) {
     if ((pool_y || pool_am) && !(pool_y && pool_am && fwd_like_fuses_pool(g, plan)))
         return set_error(WAP_EINVAL, "internal: fused pooling not available for this plan");
+    if (unpool_am && !fwd_like_fuses_unpool(g, plan))
+        return set_error(WAP_EINVAL, "internal: fused max-pool backward not available for this plan");
     if (relu_mask && !fwd_like_fuses_mask(g, plan)) {
         // no fused epilogue for this tile configuration: plain product, then the element-wise mask
         int rc = launch_fwd_like(g, b_tr, plan, A, Bw, bias, relu, out, ws, st, ev_mid, nullptr, ev_packed, prepacked);
@@ -487,7 +489,7 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
         }
         if (ev_packed) (void)hipEventRecord(ev_packed, st);
         return plan.cfg == 6 ? launch_patch(g, A, wp, bias, relu, out, st, relu_mask)
-                             : launch_tile2d(g, A, wp, bias, relu, out, st, relu_mask, pool_y, pool_am);
+                             : launch_tile2d(g, A, wp, bias, relu, out, st, relu_mask, pool_y, pool_am, unpool_am);
     }
     if (plan.cfg == 5) {
         // the (small) weight tensor is first repacked into MFMA fragment order (taps flipped and
@@ -550,14 +552,15 @@ bool fwd_like_packs_weights(const GemmPlan& plan) { return plan.cfg == 5 || plan
 bool fwd_like_fuses_pool(const GemmGeom& g, const GemmPlan& plan) {
     return plan.cfg == 7 && (g.OH % 2) == 0 && (g.OW % 2) == 0 && tile2d_fuses_pool(g);
 }
+bool fwd_like_fuses_unpool(const GemmGeom& g, const GemmPlan& plan) { return plan.cfg == 7 && tile2d_fuses_unpool(g); }
 bool fwd_like_fuses_mask(const GemmGeom& g, const GemmPlan& plan) {
     return (plan.cfg == 6 || plan.cfg == 7) && (g.Ncols % 8) == 0;
 }
 // Label of the kernel instantiation a plan launches (matches the demangled kernel name).
-const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan) {
+const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan, bool unpool) {
     if (plan.cfg == 5) return "conv_wreg_kernel";
     if (plan.cfg == 6) return patch_kernel_name(g);
-    if (plan.cfg == 7) return tile2d_kernel_name(g);
+    if (plan.cfg == 7) return tile2d_kernel_name(g, unpool);
     if (plan.cfg == 8) return conv_c3_fwd_kernel_name(g);
     static const char* names[5][2][3] = {
         {{"igemm_kernel<256,256,2,4,false,0>", "", ""}, {"igemm_kernel<256,256,2,4,true,0>", "", ""}},

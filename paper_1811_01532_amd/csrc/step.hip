@@ -35,6 +35,8 @@ struct Op {
     bool prepacked = false;  // weights of this operation are repacked once per step by the OP_PACK operation (copy at t4)
     size_t t0 = 0, t1 = 0, t2 = 0, t3 = 0, t4 = 0, t5 = 0;  // arena offsets, meaning per kind
     bool has_pool = false;  // conv forward whose epilogue also emits the 2x2 max-pool (y_pool at t3, argmax at t5)
+    bool unpool = false;    // conv backward whose dy operand is the gradient of the 2x2-pooled output, routed through the
+                            // argmax by the kernel's loader (argmax at t5 for the data gradient, t3 for the weight gradient)
     int N = 0, H = 0, W = 0, C = 0, win = 0, st = 0;  // pooling / softmax shapes
     size_t n = 0;
     const char* kernel = "";  // kernel instantiation the operation launches
@@ -115,11 +117,13 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
                                    op.has_mask ? (const bf16_t*)(base + op.t3) : nullptr, ev_packed,
                                    op.prepacked ? (const void*)(base + op.t4) : nullptr,
                                    op.has_pool ? (bf16_t*)(base + op.t3) : nullptr,
-                                   op.has_pool ? (uint8_t*)(base + op.t5) : nullptr);
+                                   op.has_pool ? (uint8_t*)(base + op.t5) : nullptr,
+                                   op.unpool ? (const uint8_t*)(base + op.t5) : nullptr);
         case OP_CONV_WGRAD:
         case OP_FC_DW:
             return launch_wgrad(op.wg, op.wp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
-                                (float*)(base + op.t2), ws, st, ev_mid);
+                                (float*)(base + op.t2), ws, st, ev_mid,
+                                op.unpool ? (const uint8_t*)(base + op.t3) : nullptr);
         case OP_POOL_FWD:
             return launch_maxpool_fwd(op.N, op.H, op.W, op.C, op.win, op.st, (const bf16_t*)(base + op.t0),
                                       (bf16_t*)(base + op.t1), (uint8_t*)(base + op.t2), st);
@@ -365,7 +369,24 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         const wap_conv_desc& d = cds[i];
         GemmGeom gf = geom_conv_fwd(d);
         if (!keep) gsel = (g_cur == gbuf[0]) ? 1 : 0;
-        if (convs[i].pool_win) {
+        // conv -> ReLU -> 2x2 pool, backward: where both backward kernels of this layer can route the pooled gradient
+        // through the argmax in their own loaders, the full-size gradient is never written.  The ReLU derivative then
+        // rides on the producer of the pooled gradient (the routed value is the window's maximum, so the pooled
+        // activation decides it).  The kept-gradients layout keeps the steps apart for inspection.
+        bool unpool = false;
+        if (!keep && convs[i].pool_win == 2 && convs[i].pool_st == 2 && (gf.OH % 2) == 0 && (gf.OW % 2) == 0) {
+            const WgradGeom wgm = geom_conv_wgrad(d);
+            const GemmGeom dgm = geom_conv_dgrad(d);
+            unpool = wgrad_fuses_unpool(wgm, plan_wgrad(wgm)) &&
+                     (i == 0 || fwd_like_fuses_unpool(dgm, plan_fwd_like(dgm, true)));
+        }
+        if (unpool) {
+            Op& prod = p->ops.back();  // the data gradient of the layer above (conv or fc6): it wrote g_cur
+            prod.has_mask = true;
+            prod.t3 = pool_y[i];
+            prod.name += "+relu_bwd";
+            prod.bytes += 2.0 * pool_y_elems[i];
+        } else if (convs[i].pool_win) {
             Op op;
             op.kind = OP_POOL_BWD; op.name = nm + ".pool_relu_bwd";
             op.N = B; op.H = gf.OH; op.W = gf.OW; op.C = d.K; op.win = convs[i].pool_win; op.st = convs[i].pool_st;
@@ -388,6 +409,14 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         }
         size_t x_in = i == 0 ? t_input : (convs[i - 1].pool_win ? pool_y[i - 1] : conv_y[i - 1]);
         push_wgrad(OP_CONV_WGRAD, nm + ".wgrad", geom_conv_wgrad(d), x_in, g_cur, p->dw_off + poff[i] * 4);
+        if (unpool) {
+            Op& wgop = p->ops.back();
+            wgop.unpool = true;
+            wgop.t3 = pool_am[i];
+            wgop.name = nm + ".unpool+wgrad";
+            wgop.kernel = wgrad_kernel_name(wgop.wg, wgop.wp, true);
+            wgop.bytes += 3.0 * pool_y_elems[i] - 2.0 * conv_y_elems[i];
+        }
         if (i > 0) {  // the gradient w.r.t. the input image is not needed
             if (!keep) gsel = (g_cur == gbuf[0]) ? 1 : 0;
             std::string in_name = "g." + lname(i - 1) + (convs[i - 1].pool_win ? ".pool.y" : ".y");
@@ -398,10 +427,17 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             // this data gradient's epilogue; the kept-gradients layout keeps the two steps apart for inspection.
             relu_done = false;
             Op& dg = p->ops.back();
+            if (unpool) {
+                dg.unpool = true;
+                dg.t5 = pool_am[i];
+                dg.name = nm + ".unpool+dgrad";
+                dg.kernel = fwd_like_kernel_name(dg.gg, true, dg.gp, true);
+                dg.bytes += 3.0 * pool_y_elems[i] - 2.0 * conv_y_elems[i];
+            }
             if (!keep && !convs[i - 1].pool_win && fwd_like_fuses_mask(dg.gg, dg.gp)) {
                 dg.has_mask = true;
                 dg.t3 = conv_y[i - 1];
-                dg.name = nm + ".dgrad+relu_bwd";
+                dg.name += "+relu_bwd";
                 dg.bytes += 2.0 * conv_y_elems[i - 1];
                 relu_done = true;
             }

@@ -17,6 +17,7 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // one 16-byte load/store as an SSA value
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;  // one 8-byte load
 
 // exact floor(x / d) for 0 <= x < 2^31 by multiply-high and shift (d >= 1)
 struct FastDiv {
@@ -76,7 +77,10 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
                     hipEvent_t ev_packed = nullptr,      // recorded after the weight repacking, if the plan has one
                     const void* prepacked = nullptr,     // weights already in packed order: skip the repacking
                     bf16_t* pool_y = nullptr,            // 2x2 / stride-2 max-pool of the output from the same epilogue
-                    uint8_t* pool_am = nullptr);         // (only where fwd_like_fuses_pool; `out` may then be NULL)
+                    uint8_t* pool_am = nullptr,          // (only where fwd_like_fuses_pool; `out` may then be NULL)
+                    const uint8_t* unpool_am = nullptr); // A is the gradient of the 2x2 / stride-2 pooled tensor and this the
+                                                         // pool's argmax (only where fwd_like_fuses_unpool)
+bool fwd_like_fuses_unpool(const GemmGeom& g, const GemmPlan& plan);
 bool fwd_like_fuses_pool(const GemmGeom& g, const GemmPlan& plan);
 bool fwd_like_packs_weights(const GemmPlan& plan);
 bool fwd_like_fuses_mask(const GemmGeom& g, const GemmPlan& plan);  // mask applied in the kernel's own epilogue?
@@ -91,14 +95,20 @@ struct WgradPlan {
     size_t ws_bytes;
 };
 WgradPlan plan_wgrad(const WgradGeom& g);
+// unpool_am: dy is the gradient of the 2x2 / stride-2 max-pooled output (N x P/2 x Q/2 x K) and unpool_am the pool's
+// argmax; only where wgrad_fuses_unpool() says so.
 int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
-                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid = nullptr);
+                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid = nullptr, const uint8_t* unpool_am = nullptr);
+bool wgrad_fuses_unpool(const WgradGeom& g, const WgradPlan& plan);
+const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan, bool unpool);
 
 // stride-1 3x3 weight gradient with the input patch resident in LDS (wgrad_patch.hip)
 bool wgrad_patch_supported(const WgradGeom& g);
 int wgrad_patch_nsplit(const WgradGeom& g);
-const char* wgrad_patch_kernel_name(const WgradGeom& g);
-int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* out, hipStream_t st);
+bool wgrad_patch_fuses_unpool(const WgradGeom& g);
+const char* wgrad_patch_kernel_name(const WgradGeom& g, bool unpool);
+int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* out, hipStream_t st,
+                       const uint8_t* unpool_am = nullptr);
 
 // 3-input-channel 3x3 stride-1 first layer (conv_c3.hip)
 bool conv_c3_fwd_supported(const GemmGeom& g);
@@ -139,12 +149,14 @@ int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float
 // stride-1 convolution on 8 x 32-pixel 2-D tiles for 64 / 128 output channels (conv_tile2d.hip)
 int tile2d_supported(const GemmGeom& g);
 bool tile2d_preferred(const GemmGeom& g);
-const char* tile2d_kernel_name(const GemmGeom& g);
+const char* tile2d_kernel_name(const GemmGeom& g, bool unpool);
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                  hipStream_t st, const bf16_t* mask = nullptr, bf16_t* pool_y = nullptr, uint8_t* pool_am = nullptr);
+                  hipStream_t st, const bf16_t* mask = nullptr, bf16_t* pool_y = nullptr, uint8_t* pool_am = nullptr,
+                  const uint8_t* unpool_am = nullptr);
 bool tile2d_fuses_pool(const GemmGeom& g);
+bool tile2d_fuses_unpool(const GemmGeom& g);
 
-const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan);
+const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& plan, bool unpool = false);
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan);
 
 // split-reduction epilogues (fixed summation order)

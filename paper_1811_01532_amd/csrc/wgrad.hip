@@ -310,7 +310,9 @@ WgradPlan plan_wgrad(const WgradGeom& g) {
 }
 
 int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
-                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid) {
+                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid, const uint8_t* unpool_am) {
+    if (unpool_am && !wgrad_fuses_unpool(g, plan))
+        return set_error(WAP_EINVAL, "internal: fused max-pool backward not available for this weight gradient");
     WArgs wa;
     wa.x = x;
     wa.dy = dy;
@@ -333,7 +335,7 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
         return launch_reduce_f32(reinterpret_cast<const float*>(ws), plan.nsplit, (size_t)g.K * wa.Kred, dw, st);
     }
     if (plan.cfg == 3) {
-        int rc3 = launch_wgrad_patch(g, plan.nsplit, x, dy, wa.out, st);
+        int rc3 = launch_wgrad_patch(g, plan.nsplit, x, dy, wa.out, st, unpool_am);
         if (rc3 != WAP_OK) return rc3;
         if (ev_mid) (void)hipEventRecord(ev_mid, st);
         if (plan.nsplit > 1)
@@ -363,8 +365,12 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
 }  // namespace wap
 
 namespace wap {
-const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan) {
-    if (plan.cfg == 3) return wgrad_patch_kernel_name(g);
+bool wgrad_fuses_unpool(const WgradGeom& g, const WgradPlan& plan) {
+    return plan.cfg == 3 && wgrad_patch_fuses_unpool(g);
+}
+const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan) { return wgrad_kernel_name(g, plan, false); }
+const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan, bool unpool) {
+    if (plan.cfg == 3) return wgrad_patch_kernel_name(g, unpool);
     if (plan.cfg == 4) return wgrad_c3_kernel_name(g);
     static const char* names[3][2] = {
         {"wgrad_kernel<256,256,2,4,0>", ""},

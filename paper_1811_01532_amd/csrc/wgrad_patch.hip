@@ -18,6 +18,9 @@
 //     written to the other buffer, so a tile costs one barrier and no exposed load or store phase;
 //   * the pixel range is split across work-groups; every split writes an fp32 partial and the reduce
 //     kernel adds them in a fixed order (bitwise reproducible).
+// UP variant: dy is given as the gradient of a 2x2 / stride-2 max-pool OUTPUT plus the pool's argmax; the
+// loader routes each window's value to the pixel the argmax names (the max-pool backward of the auxiliary
+// node between two primary nodes, Section 3.2.2) on the way into LDS, so the full-size dy never exists.
 #include "wap_internal.h"
 
 namespace wap {
@@ -45,6 +48,10 @@ struct WPArgs {
     int kgroups, ncombo, nsplit, tiles_per_split;
     int buf_bytes, d_off;       // bytes per LDS tile buffer, offset of the dy tile inside it
     unsigned x_bytes, dy_bytes;
+    const uint8_t* am;  // UP: argmax (r * 2 + s) of every pooling window, same shape as the pooled dy
+    int P2, Q2;         // UP: pooled map size
+    int VW2, units;     // UP: pooling windows per virtual tile row, windows per dy tile (all 16 * nk16 rows covered)
+    FastDiv dVW2;
     FastDiv dVW, dPWp, dTimg, dTx;
 };
 
@@ -62,8 +69,21 @@ __device__ __forceinline__ bf16x8 tr_pair(const unsigned char* p0, const unsigne
     return __builtin_bit_cast(bf16x8, both);
 }
 
-// FD: 32-channel dy blocks per wavefront; the work-group covers 64 * FD output channels
-template <int FD>
+// keeps the bf16 lanes of the pooled gradient v whose window's argmax byte equals this pixel's position code
+__device__ __forceinline__ u32x4 unpool_select8(u32x4 v, u32x2 am, unsigned code) {
+    const unsigned c4 = code * 0x01010101u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const unsigned x = ((k < 2 ? am[0] : am[1]) >> ((k & 1) * 16)) ^ c4;  // a zero byte where argmax == code
+        const unsigned lo = (x & 0xffu) == 0u ? 0xffffu : 0u;
+        const unsigned hi = (x & 0xff00u) == 0u ? 0xffff0000u : 0u;
+        v[k] &= (lo | hi);
+    }
+    return v;
+}
+
+// FD: 32-channel dy blocks per wavefront; the work-group covers 64 * FD output channels.  UP: dy arrives pooled.
+template <int FD, bool UP>
 __global__ __launch_bounds__(NT, 3) void wgrad_patch_kernel(const WPArgs a) {
     constexpr int KO = 64 * FD;             // output channels per work-group
     constexpr int DPITCH = KO * 2 + 64;     // same bank argument as XPITCH
@@ -86,11 +106,16 @@ __global__ __launch_bounds__(NT, 3) void wgrad_patch_kernel(const WPArgs a) {
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a.x), 0, (int)a.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcD =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a.dy), 0, (int)a.dy_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcM =  // one argmax byte per pooled element: half the bytes of the pooled dy
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(UP ? a.am : nullptr), 0, UP ? (int)(a.dy_bytes / 2) : 0, 0x00020000);
 
     // ---- global loads of one tile.  The slot geometry (which padded pixel / dy pixel a thread fetches) is
     // recomputed from the thread index for every tile: hoisted out of the tile loop it would sit in registers
     // the accumulators need, and come back as scratch reloads on the critical path of every tile. ----
-    u32x4 rp[PV], rd[DV];
+    // UP: a thread fetches one whole pooling window (16 bytes of pooled dy, 8 argmax bytes) and writes its four pixels;
+    // the tile has even origin and size, so windows never straddle tiles
+    u32x4 rp[PV], rd[UP ? 1 : DV];
+    u32x2 ra[1];
     auto load_tile = [&](int t) {
         int tv = tid;
         asm volatile("" : "+v"(tv));  // opaque copy: keeps the slot arithmetic inside the loop
@@ -109,14 +134,24 @@ __global__ __launch_bounds__(NT, 3) void wgrad_patch_kernel(const WPArgs a) {
             const unsigned off = (xbase + (unsigned)((ih * g.W + iw) * g.C)) * 2u;
             rp[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcX, ok ? off : OOB, 0, 0);
         }
-        const unsigned dbase = (unsigned)(((img * g.P + oh0) * g.Q + ow0) * g.K + ko0 + (tv % DVP) * 8);
+        if (UP) {
+            const int unit = tv / DVP;
+            const int uy = (int)fdiv((uint32_t)unit, a.dVW2), ux = unit - uy * a.VW2;
+            const bool ok = 2 * uy < a.TH && 2 * ux < a.TWr;
+            const unsigned el =  // pooled element
+                (unsigned)(((img * a.P2 + (oh0 >> 1) + uy) * a.Q2 + (ow0 >> 1) + ux) * g.K + ko0 + (tv % DVP) * 8);
+            rd[0] = __builtin_amdgcn_raw_buffer_load_b128(rsrcD, ok ? el * 2u : OOB, 0, 0);
+            ra[0] = __builtin_amdgcn_raw_buffer_load_b64(rsrcM, ok ? el : OOB, 0, 0);
+        } else {
+            const unsigned dbase = (unsigned)(((img * g.P + oh0) * g.Q + ow0) * g.K + ko0 + (tv % DVP) * 8);
 #pragma unroll
-        for (int i = 0; i < DV; ++i) {
-            const int q = tv / DVP + i * (NT / DVP);
-            const int ty = (int)fdiv((uint32_t)q, a.dVW), tx = q - ty * a.VW;
-            const bool ok = ty < a.TH && tx < a.TWr;
-            const unsigned off = (dbase + (unsigned)((ty * g.Q + tx) * g.K)) * 2u;
-            rd[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcD, ok ? off : OOB, 0, 0);
+            for (int i = 0; i < DV; ++i) {
+                const int q = tv / DVP + i * (NT / DVP);
+                const int ty = (int)fdiv((uint32_t)q, a.dVW), tx = q - ty * a.VW;
+                const bool ok = ty < a.TH && tx < a.TWr;
+                const unsigned off = (dbase + (unsigned)((ty * g.Q + tx) * g.K)) * 2u;
+                rd[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcD, ok ? off : OOB, 0, 0);
+            }
         }
     };
     // rows [0, patch_len) of the patch and [0, 16 * nk16) of the dy tile are (re)written for every tile, so
@@ -129,10 +164,27 @@ __global__ __launch_bounds__(NT, 3) void wgrad_patch_kernel(const WPArgs a) {
             const int q = (tid >> 3) + i * (NT / 8);
             if (q < a.patch_len) *reinterpret_cast<u32x4*>(sX + q * XPITCH + (tid & 7) * 16) = rp[i];
         }
+        if (UP) {
+            int tv = tid;
+            asm volatile("" : "+v"(tv));  // opaque copy: the window's row addresses are recomputed per tile, not kept
+            const int unit = tv / DVP;
+            const int uy = (int)fdiv((uint32_t)unit, a.dVW2), ux = unit - uy * a.VW2;
+            if (unit < a.units) {
 #pragma unroll
-        for (int i = 0; i < DV; ++i) {
-            const int q = tid / DVP + i * (NT / DVP);
-            if (q < a.nk16 * 16) *reinterpret_cast<u32x4*>(sD + q * DPITCH + (tid % DVP) * 16) = rd[i];
+                for (int pos = 0; pos < 4; ++pos) {
+                    const int q = (2 * uy + (pos >> 1)) * a.VW + 2 * ux + (pos & 1);
+                    if (q < a.nk16 * 16)
+                        *reinterpret_cast<u32x4*>(sD + q * DPITCH + (tv % DVP) * 16) =
+                            unpool_select8(rd[0], ra[0], (unsigned)pos);
+                    __builtin_amdgcn_sched_barrier(0);  // one pixel at a time: four selected copies at once do not fit
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < DV; ++i) {
+                const int q = tid / DVP + i * (NT / DVP);
+                if (q < a.nk16 * 16) *reinterpret_cast<u32x4*>(sD + q * DPITCH + (tid % DVP) * 16) = rd[i];
+            }
         }
     };
 
@@ -255,8 +307,21 @@ bool wgrad_patch_supported(const WgradGeom& g) {
     return ts.TH * ts.TWr >= 64;  // tiny tiles: the generic kernel is no worse
 }
 
-const char* wgrad_patch_kernel_name(const WgradGeom& g) {
-    return fd_for(g) == 2 ? "wgrad_patch_kernel<2>" : "wgrad_patch_kernel<1>";
+const char* wgrad_patch_kernel_name(const WgradGeom& g, bool unpool) {
+    if (unpool) return fd_for(g) == 2 ? "wgrad_patch_kernel<2,true>" : "wgrad_patch_kernel<1,true>";
+    return fd_for(g) == 2 ? "wgrad_patch_kernel<2,false>" : "wgrad_patch_kernel<1,false>";
+}
+
+// dy given as the gradient of the 2x2 / stride-2 pooled output plus the argmax: whole windows only
+static int unpool_units(const TileShape& ts) {  // windows of (2 rows x 2 columns) covering every row of the padded dy tile
+    const int rows16 = (ts.TH * ts.VW + 15) / 16 * 16;
+    return (rows16 + 2 * ts.VW - 1) / (2 * ts.VW) * (ts.VW / 2);
+}
+bool wgrad_patch_fuses_unpool(const WgradGeom& g) {
+    TileShape ts;
+    if (!wgrad_patch_supported(g) || (g.P % 2) != 0 || (g.Q % 2) != 0 || !choose_tile(g, &ts)) return false;
+    if ((ts.TH % 2) != 0 || (ts.TWr % 2) != 0) return false;  // windows must not straddle tiles
+    return unpool_units(ts) * (64 * fd_for(g) / 8) <= NT;      // one window vector per thread
 }
 
 int wgrad_patch_nsplit(const WgradGeom& g) {
@@ -271,12 +336,21 @@ int wgrad_patch_nsplit(const WgradGeom& g) {
     return (int)((tiles + tps - 1) / tps);
 }
 
-int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* out, hipStream_t st) {
+int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* out, hipStream_t st,
+                       const uint8_t* unpool_am) {
     WPArgs wa;
     TileShape ts;
     if (!wgrad_patch_supported(g) || !choose_tile(g, &ts))
         return set_error(WAP_EINVAL, "internal: patch weight-gradient kernel not applicable");
+    if (unpool_am && !wgrad_patch_fuses_unpool(g))
+        return set_error(WAP_EINVAL, "internal: fused max-pool backward not available for this shape");
     const int fd = fd_for(g);
+    wa.am = unpool_am;
+    wa.P2 = g.P / 2;
+    wa.Q2 = g.Q / 2;
+    wa.VW2 = ts.VW / 2;
+    wa.units = unpool_units(ts);
+    wa.dVW2 = make_fastdiv((uint32_t)wa.VW2);
     wa.x = x;
     wa.dy = dy;
     wa.out = out;
@@ -299,7 +373,7 @@ int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf
     wa.d_off = wa.patch_len * XPITCH;
     wa.buf_bytes = (int)buf_bytes_for(fd, wa.patch_len, wa.nk16);
     wa.x_bytes = (unsigned)((size_t)g.N * g.H * g.W * g.C * 2);
-    wa.dy_bytes = (unsigned)((size_t)g.N * g.P * g.Q * g.K * 2);
+    wa.dy_bytes = (unsigned)((size_t)g.N * g.P * g.Q * g.K * 2 / (unpool_am ? 4 : 1));
     wa.dVW = make_fastdiv((uint32_t)wa.VW);
     wa.dPWp = make_fastdiv((uint32_t)wa.PWp);
     wa.dTimg = make_fastdiv((uint32_t)wa.tiles_img);
@@ -308,14 +382,21 @@ int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf
     if (smem > LDS_BYTES) return set_error(WAP_EINVAL, "internal: patch weight-gradient tile does not fit LDS");
     static bool attr_done = false;
     if (!attr_done) {
-        for (const void* f : {(const void*)wgrad_patch_kernel<1>, (const void*)wgrad_patch_kernel<2>}) {
+        for (const void* f : {(const void*)wgrad_patch_kernel<1, false>, (const void*)wgrad_patch_kernel<2, false>,
+                              (const void*)wgrad_patch_kernel<1, true>, (const void*)wgrad_patch_kernel<2, true>}) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
             if (e != hipSuccess) return set_error(WAP_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
         }
         attr_done = true;
     }
-    if (fd == 1) hipLaunchKernelGGL(wgrad_patch_kernel<1>, dim3(wa.ncombo * nsplit), dim3(NT), smem, st, wa);
-    else hipLaunchKernelGGL(wgrad_patch_kernel<2>, dim3(wa.ncombo * nsplit), dim3(NT), smem, st, wa);
+    const dim3 grid(wa.ncombo * nsplit);
+    if (unpool_am) {
+        if (fd == 1) hipLaunchKernelGGL((wgrad_patch_kernel<1, true>), grid, dim3(NT), smem, st, wa);
+        else hipLaunchKernelGGL((wgrad_patch_kernel<2, true>), grid, dim3(NT), smem, st, wa);
+    } else {
+        if (fd == 1) hipLaunchKernelGGL((wgrad_patch_kernel<1, false>), grid, dim3(NT), smem, st, wa);
+        else hipLaunchKernelGGL((wgrad_patch_kernel<2, false>), grid, dim3(NT), smem, st, wa);
+    }
     return check_launch("wgrad_patch");
 }
 

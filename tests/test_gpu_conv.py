@@ -48,6 +48,9 @@ CASES = [
     ("wgrad_patch_w14_masked_columns", (3, 14, 14, 128, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("wgrad_patch_w28_forced_split5", (1, 28, 28, 64, 128, 3, 3, 1, 1), (-1, 3, 5)),
     ("wgrad_patch_pad0_w30", (2, 34, 32, 64, 64, 3, 3, 1, 0), (-1, -1, -1)),
+    # backward through a 2x2 pool routed in the loaders: flat data-gradient tiles, two dy blocks per wavefront
+    ("unpool_flat_w14_c128_k128", (5, 14, 14, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
+    ("unpool_w112_c64_k128", (1, 32, 112, 64, 128, 3, 3, 1, 1), (-1, -1, -1)),
     # 3-input-channel first-layer kernels: ragged last tile / step, 32 and 64 output channels, pad 0
     ("c3_k64_ragged", (3, 41, 40, 3, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("c3_k32", (2, 48, 48, 3, 32, 3, 3, 1, 1), (-1, -1, -1)),
@@ -149,6 +152,50 @@ def test_conv_three_passes_match_oracle(orc, name, shape, force):
         wap.wap_conv2d_bwd_weight(d, xd, gd, dw2, ws)
         torch.cuda.synchronize()
         assert torch.equal(dw, dw2)
+        # ---- both backward passes with dy given as the gradient of the 2x2 / stride-2 pooled output plus the pool's
+        # argmax: against the oracle's max-pool backward followed by its data / weight gradient, and bit for bit
+        # against the device's own unfused chain; where the loader routes the gradient itself, also without the
+        # full-size scratch tensor ----
+        if P % 2 == 0 and Q % 2 == 0:
+            gpb = si.normal_bf16(si.rng(100 + ci, 4), (N, P // 2, Q // 2, K))
+            amh = si.rng(100 + ci, 5).integers(0, 4, size=(N, P // 2, Q // 2, K), dtype=np.uint8)
+            gpd, amd = gu.dev_bf16(gpb), torch.from_numpy(amh).cuda()
+            routed64 = orc.maxpool_bwd(orc.bf16_bits_to_f64(gpb), amh, (N, P, Q, K), 2, 2)
+            dyf = torch.full((N, P, Q, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+            wap.wap_maxpool_bwd(N, P, Q, K, 2, 2, gpd, amd, None, dyf)
+            torch.cuda.synchronize()
+            assert np.array_equal(gu.host_f64(dyf), routed64)
+            wsd = gu.workspace(wap.wap_conv2d_workspace_bytes(d, wap.WAP_PASS_BWD_DATA))
+            wsw = gu.workspace(wap.wap_conv2d_workspace_bytes(d, wap.WAP_PASS_BWD_WEIGHT))
+            dxu = torch.full((N, H, W, C), float("nan"), dtype=torch.bfloat16, device="cuda")
+            wap.wap_conv2d_bwd_data_relu(d, dyf, wd, xact, dxu, wsd)
+            dwu = torch.full((K, R, S, C), float("nan"), dtype=torch.float32, device="cuda")
+            wap.wap_conv2d_bwd_weight(d, xd, dyf, dwu, wsw)
+            torch.cuda.synchronize()
+            refdx_p = orc.relu_bwd(orc.conv2d_bwd_data(routed64, w64, (N, H, W, C), stride, pad), np.maximum(x64, 0.0))
+            refdw_p = orc.conv2d_bwd_weight(x64, routed64, (K, R, S, C), stride, pad)
+            fused = (wap.wap_conv2d_bwd_pool2x2_fused(d, wap.WAP_PASS_BWD_DATA),
+                     wap.wap_conv2d_bwd_pool2x2_fused(d, wap.WAP_PASS_BWD_WEIGHT))
+            print(f"[case] {name} unpool fused (dgrad, wgrad) = {fused}", flush=True)
+            for with_scratch in (True, False):
+                scratch = torch.full((N, P, Q, K), float("nan"), dtype=torch.bfloat16, device="cuda") if with_scratch else None
+                if with_scratch or fused[0]:
+                    dxp = torch.full((N, H, W, C), float("nan"), dtype=torch.bfloat16, device="cuda")
+                    wap.wap_conv2d_bwd_data_pool2x2(d, gpd, amd, wd, xact, dxp, scratch, wsd)
+                    torch.cuda.synchronize()
+                    e = gu.rel_err(gu.host_f64(dxp), refdx_p)
+                    assert e <= gu.TOL and e <= gu.TOL_BF16_OUT, f"unpool+dgrad rel err {e}"
+                    assert torch.equal(dxp, dxu)
+                if with_scratch or fused[1]:
+                    dwp = torch.full((K, R, S, C), float("nan"), dtype=torch.float32, device="cuda")
+                    wap.wap_conv2d_bwd_weight_pool2x2(d, xd, gpd, amd, dwp, scratch, wsw)
+                    torch.cuda.synchronize()
+                    e = gu.rel_err(gu.host_f64(dwp), refdw_p)
+                    assert e <= gu.TOL and e <= gu.TOL_F32_OUT, f"unpool+wgrad rel err {e}"
+                    assert torch.equal(dwp, dwu)
+            if not fused[0]:
+                with pytest.raises(wap.WapError):
+                    wap.wap_conv2d_bwd_data_pool2x2(d, gpd, amd, wd, xact, dxu, None, wsd)
     finally:
         wap.lib().wap_debug_force(-1, -1, -1)
 
