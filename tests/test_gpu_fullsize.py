@@ -124,3 +124,79 @@ def test_fc_layer_full_size_sampled(orc, name, B, n_in, n_out):
     ref = orc.fc_bwd_weight(np.ascontiguousarray(g64[:, cols]), np.ascontiguousarray(x64[:, icols]))
     e = gu.rel_err(gu.host_f64(dW)[np.ix_(cols, icols)], ref)
     assert e <= gu.TOL and e <= gu.TOL_F32_OUT, f"{name} dW rel err {e}"
+
+
+# VGG-16 layers that are followed by a 2x2 pool, at per-GPU minibatch 64: name, N, H, C, K
+POOLED = [
+    ("vgg_conv1_2_b64", 64, 224, 64, 64),
+    ("vgg_conv2_2_b64", 64, 112, 128, 128),
+    ("vgg_conv3_3_b64", 64, 56, 256, 256),
+    ("vgg_conv4_3_b64", 64, 28, 512, 512),
+]
+
+
+@pytest.mark.parametrize("name,N,H,C,K", POOLED, ids=[l[0] for l in POOLED])
+def test_pooled_layer_fused_paths_full_size(orc, name, N, H, C, K):
+    """The conv -> ReLU -> 2x2 pool chain as the step plan runs it: pool taken in the forward kernel's epilogue, pool
+    backward routed in the loaders of both backward kernels.  Each fused call is compared bit for bit with the
+    device's own unfused chain, and the backward results on sampled coordinates with the oracle (max-pool backward,
+    then one dot product per sample)."""
+    import paper_1811_01532_amd as wap
+    li = [l[0] for l in POOLED].index(name)
+    print(f"[case] full-size fused pool paths {name}", flush=True)
+    xb = si.normal_bf16(si.rng(800 + li, 0), (N, H, H, C))
+    wb = si.he_weight_bf16(si.rng(800 + li, 1), (K, 3, 3, C))
+    gpb = si.normal_bf16(si.rng(800 + li, 2), (N, H // 2, H // 2, K))
+    amh = si.rng(800 + li, 3).integers(0, 4, size=(N, H // 2, H // 2, K), dtype=np.uint8)
+    xd, wd, gpd, amd = gu.dev_bf16(xb), gu.dev_bf16(wb), gu.dev_bf16(gpb), torch.from_numpy(amh).cuda()
+    d = wap.conv_desc(N, H, H, C, K, 3, 3, 1, 1, relu=True)
+    ws = gu.workspace(max(wap.wap_conv2d_workspace_bytes(d, p) for p in (0, 1, 2)))
+    # ---- forward + pool ----
+    y = torch.empty((N, H, H, K), dtype=torch.bfloat16, device="cuda")
+    yp = torch.empty((N, H // 2, H // 2, K), dtype=torch.bfloat16, device="cuda")
+    am = torch.empty((N, H // 2, H // 2, K), dtype=torch.uint8, device="cuda")
+    wap.wap_conv2d_fwd(d, xd, wd, None, y, ws)
+    wap.wap_maxpool_fwd(N, H, H, K, 2, 2, y, yp, am)
+    if wap.wap_conv2d_fwd_pool2x2_fused(d):
+        yp2, am2 = torch.full_like(yp, float("nan")), torch.full_like(am, 77)
+        wap.wap_conv2d_fwd_pool2x2(d, xd, wd, None, None, yp2, am2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(yp2, yp) and torch.equal(am2, am), f"{name}: fused forward pool differs"
+        del yp2, am2
+    del y, yp, am
+    # ---- backward through the pool ----
+    fused = (wap.wap_conv2d_bwd_pool2x2_fused(d, wap.WAP_PASS_BWD_DATA),
+             wap.wap_conv2d_bwd_pool2x2_fused(d, wap.WAP_PASS_BWD_WEIGHT))
+    assert fused == (True, True), f"{name}: the benchmark's launch list expects both passes fused, got {fused}"
+    xact = torch.relu(xd)
+    dyf = torch.empty((N, H, H, K), dtype=torch.bfloat16, device="cuda")
+    wap.wap_maxpool_bwd(N, H, H, K, 2, 2, gpd, amd, None, dyf)
+    dxu = torch.empty((N, H, H, C), dtype=torch.bfloat16, device="cuda")
+    dwu = torch.empty((K, 3, 3, C), dtype=torch.float32, device="cuda")
+    wap.wap_conv2d_bwd_data_relu(d, dyf, wd, xact, dxu, ws)
+    wap.wap_conv2d_bwd_weight(d, xd, dyf, dwu, ws)
+    del dyf
+    dxp = torch.full_like(dxu, float("nan"))
+    dwp = torch.full_like(dwu, float("nan"))
+    wap.wap_conv2d_bwd_data_pool2x2(d, gpd, amd, wd, xact, dxp, None, ws)
+    wap.wap_conv2d_bwd_weight_pool2x2(d, xd, gpd, amd, dwp, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dxp, dxu), f"{name}: fused unpool + data gradient differs from the unfused chain"
+    assert torch.equal(dwp, dwu), f"{name}: fused unpool + weight gradient differs from the unfused chain"
+    dxh = dxp.view(torch.int16).cpu().numpy().view(np.uint16).ravel()
+    dwh = dwp.cpu().numpy().astype(np.float64).ravel()
+    del xd, xact, dxu, dxp, gpd, amd
+    torch.cuda.empty_cache()
+    # ---- oracle on samples ----
+    x64, w64 = orc.bf16_bits_to_f64(xb), orc.bf16_bits_to_f64(wb)
+    routed = orc.maxpool_bwd(orc.bf16_bits_to_f64(gpb), amh, (N, H, H, K), 2, 2)
+    rng = np.random.default_rng(900 + li)
+    ix = _border_indices((N, H, H, C), rng, 4096)
+    ref = orc.conv2d_bwd_data_at(routed, w64, (N, H, H, C), ix, (1, 1), (1, 1))
+    ref = np.where(x64.ravel()[ix] > 0.0, ref, 0.0)
+    e = gu.rel_err(orc.bf16_bits_to_f64(dxh[ix]), ref)
+    assert e <= gu.TOL and e <= gu.TOL_BF16_OUT, f"{name} unpool+dgrad sampled rel err {e}"
+    iw = np.unique(rng.integers(0, K * 9 * C, 256 if N * H * H > 500000 else 1024)).astype(np.int64)
+    ref = orc.conv2d_bwd_weight_at(x64, routed, (K, 3, 3, C), iw, (1, 1), (1, 1))
+    e = gu.rel_err(dwh[iw], ref)
+    assert e <= gu.TOL and e <= gu.TOL_F32_OUT, f"{name} unpool+wgrad sampled rel err {e}"
