@@ -137,7 +137,7 @@ __global__ __launch_bounds__(NT, 3) void wgrad_patch_kernel(const WPArgs a) {
         if (UP) {
             const int unit = tv / DVP;
             const int uy = (int)fdiv((uint32_t)unit, a.dVW2), ux = unit - uy * a.VW2;
-            const bool ok = 2 * uy < a.TH && 2 * ux < a.TWr;
+            const bool ok = 2 * uy < a.TH && 2 * ux < a.TWr && oh0 + 2 * uy < g.P;
             const unsigned el =  // pooled element
                 (unsigned)(((img * a.P2 + (oh0 >> 1) + uy) * a.Q2 + (ow0 >> 1) + ux) * g.K + ko0 + (tv % DVP) * 8);
             rd[0] = __builtin_amdgcn_raw_buffer_load_b128(rsrcD, ok ? el * 2u : OOB, 0, 0);
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(NT, 3) void wgrad_patch_kernel(const WPArgs a) {
             for (int i = 0; i < DV; ++i) {
                 const int q = tv / DVP + i * (NT / DVP);
                 const int ty = (int)fdiv((uint32_t)q, a.dVW), tx = q - ty * a.VW;
-                const bool ok = ty < a.TH && tx < a.TWr;
+                const bool ok = ty < a.TH && tx < a.TWr && oh0 + ty < g.P;
                 const unsigned off = (dbase + (unsigned)((ty * g.Q + tx) * g.K)) * 2u;
                 rd[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcD, ok ? off : OOB, 0, 0);
             }
@@ -274,7 +274,8 @@ size_t buf_bytes_for(int fd, int patch_len, int nk16) {
     return (size_t)patch_len * XPITCH + (size_t)nk16 * 16 * (fd * 128 + 64);
 }
 
-// Largest tile (in real pixels) whose two LDS buffers fit; then the least padding.
+// Most real pixels per tile (the tile height need not divide the map: the last tile row of an image is then partly
+// masked) among the tiles whose two LDS buffers fit; then the least padding.
 bool choose_tile(const WgradGeom& g, TileShape* out) {
     const int fd = fd_for(g);
     long best = 0;
@@ -282,11 +283,11 @@ bool choose_tile(const WgradGeom& g, TileShape* out) {
         if (g.Q % twr) continue;
         const int vw = twr <= 16 ? 16 : (twr + 3) / 4 * 4;  // the kernel's row stepping needs at least 16 columns
         for (int th = 1; th <= g.P; ++th) {
-            if (g.P % th) continue;
+            const int tiles_y = (g.P + th - 1) / th;
             const int npix = th * vw, padded = (npix + 15) / 16 * 16, patch = (th + 2) * (vw + 2);
             if (npix > DCAP || patch > PCAP) break;
             if (2 * buf_bytes_for(fd, patch, padded / 16) > LDS_BYTES) break;
-            long score = (long)th * twr * 1024 + (1023 - (padded - th * twr));
+            long score = (long)g.P * twr * 1024 / tiles_y + (1023 - (padded - th * twr));
             if (score > best) {
                 best = score;
                 *out = {th, twr, vw};
@@ -327,9 +328,9 @@ bool wgrad_patch_fuses_unpool(const WgradGeom& g) {
 int wgrad_patch_nsplit(const WgradGeom& g) {
     TileShape ts;
     if (!choose_tile(g, &ts)) return 1;
-    const long tiles = (long)g.N * (g.P / ts.TH) * (g.Q / ts.TWr);
+    const long tiles = (long)g.N * ((g.P + ts.TH - 1) / ts.TH) * (g.Q / ts.TWr);
     const long ncombo = (long)(g.K / (64 * fd_for(g))) * (g.C / 64);
-    long want = (kNumCU + ncombo - 1) / ncombo;  // one resident work-group per CU, one round
+    long want = kNumCU / ncombo;  // one resident work-group per CU, one round (never a second, nearly empty one)
     if (want < 1) want = 1;
     if (want > tiles) want = tiles;
     const long tps = (tiles + want - 1) / want;
@@ -364,7 +365,7 @@ int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf
     wa.npix = ts.TH * ts.VW;
     wa.nk16 = (wa.npix + 15) / 16;
     wa.tiles_x = g.Q / ts.TWr;
-    wa.tiles_img = wa.tiles_x * (g.P / ts.TH);
+    wa.tiles_img = wa.tiles_x * ((g.P + ts.TH - 1) / ts.TH);
     wa.tiles_total = wa.tiles_img * g.N;
     wa.kgroups = g.K / (64 * fd);
     wa.ncombo = wa.kgroups * (g.C / 64);

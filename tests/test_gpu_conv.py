@@ -48,6 +48,8 @@ CASES = [
     ("wgrad_patch_w14_masked_columns", (3, 14, 14, 128, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("wgrad_patch_w28_forced_split5", (1, 28, 28, 64, 128, 3, 3, 1, 1), (-1, 3, 5)),
     ("wgrad_patch_pad0_w30", (2, 34, 32, 64, 64, 3, 3, 1, 0), (-1, -1, -1)),
+    ("wgrad_patch_w13_partly_masked_tile_rows", (3, 13, 13, 192, 128, 3, 3, 1, 1), (-1, -1, -1)),
+    ("wgrad_patch_h22_w12_partly_masked_even", (2, 22, 12, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
     # backward through a 2x2 pool routed in the loaders: flat data-gradient tiles, two dy blocks per wavefront
     ("unpool_flat_w14_c128_k128", (5, 14, 14, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
     ("unpool_w112_c64_k128", (1, 32, 112, 64, 128, 3, 3, 1, 1), (-1, -1, -1)),
