@@ -331,6 +331,176 @@ __global__ __launch_bounds__(NT) void wgrad_c3_kernel(const C3Args a) {
     }
 }
 
+// ---- weight gradient for a LARGE filter at a horizontal stride that is a multiple of 4 (the 11x11 stride-4
+// first layer of the AlexNet-style network): dw[ko][(r,s,c)] = sum over pixels of dy[pix][ko] * x[pix @ (r,s)][c].
+// For one output row the im2col row of pixel ow and filter row r is a CONTIGUOUS run of S*3 elements of input row
+// oh*sh - ph + r starting at element (ow*sw - pw)*3: the runs of neighbouring pixels overlap, start 6*sw bytes
+// apart, and need no gather at all once the R input rows sit in LDS: a transposing read whose lanes supply
+// "row base + 6*sw*pixel + 2*column" delivers the MFMA operand directly (6*sw is a multiple of 8 bytes, which the
+// 8-byte transposing read needs, exactly when sw is a multiple of 4).  Columns are numbered r * SC4 + (s*3 + c)
+// with SC4 = S*3 rounded up to a multiple of 4 (a 4-column chunk never straddles two filter rows); the surplus
+// columns multiply real neighbouring input elements and are dropped in the epilogue.
+// A work-group takes whole output rows (n, oh): R input rows and the dy row go to LDS, then ceil(OW/16) reduction
+// steps; wavefront w owns the 32-column blocks w, w+4, ... (at most 4) for all K output channels.  One fp32
+// partial per work-group, summed afterwards in a fixed order.
+struct C3SArgs {
+    const bf16_t* x;
+    const bf16_t* dy;
+    float* part;
+    int N, H, W, OH, OW, R, S, sh, sw, ph, pw;
+    int SC4, NB, Kred, xrowb, units, nsteps, nvx;  // columns per filter row (padded), 32-column blocks, LDS bytes per x row,
+                                                   // output rows in all, 16-pixel steps per row, 16-byte vectors per x row
+    FastDiv dOH, dSC4, dNVX;
+};
+
+template <int FB>
+__global__ __launch_bounds__(NT) void wgrad_c3_strided_kernel(const C3SArgs a) {
+    constexpr int K = 32 * FB;
+    constexpr int DPITCH = K * 2 + 64;
+    constexpr int VPR = K / 8;
+    extern __shared__ __align__(16) unsigned char smem_s[];
+    unsigned char* sX = smem_s;                 // [R][xrowb]: element e of an input row at byte 6*pw + 2*e
+    unsigned char* sD = smem_s + a.R * a.xrowb;  // [16 * nsteps][DPITCH]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int total16 = (a.R * a.xrowb + 16 * a.nsteps * DPITCH) / 16;
+    // the halo left of the row, the run-over right of it and the dy rows past OW are read but never written: zero once
+    for (int i = tid; i < total16; i += NT) *reinterpret_cast<u32x4*>(smem_s + i * 16) = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
+
+    const int kl = half * 8 + ((lane & 15) >> 2);
+    const int ccol = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;  // first of this lane's 4 columns inside a 32-column block
+    int xo[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int f = 32 * (wave + 4 * j) + ccol;
+        int r = (int)fdiv((uint32_t)f, a.dSC4);
+        const int sc = f - r * a.SC4;
+        if (r >= a.R) r = a.R - 1;  // columns past the filter: any readable address, the products are dropped
+        xo[j] = r * a.xrowb + 2 * sc + 6 * a.sw * kl;
+    }
+    f32x16 acc[4][FB];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int b = 0; b < FB; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][b][e] = 0.f;
+
+    // Row u+1 is fetched into registers while row u is multiplied out of LDS (one buffer, two barriers per row).
+    const int W3 = a.W * 3;
+    constexpr int XV = 4, DVL = 2;  // 16-byte vectors per thread: x rows (R * nvx <= 1024), dy row (OW * K / 8 <= 512)
+    u32x4 rx[XV], rdv[DVL];
+    auto load_row = [&](int u) {
+        const int n = (int)fdiv((uint32_t)u, a.dOH), oh = u - n * a.OH;
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            const int v = tid + i * NT;
+            const int r = (int)fdiv((uint32_t)v, a.dNVX), j = v - r * a.nvx;
+            const int ih = oh * a.sh - a.ph + r;
+            const bool ok = v < a.R * a.nvx && (unsigned)ih < (unsigned)a.H;
+            rx[i] = *reinterpret_cast<const u32x4*>(
+                ok ? a.x + ((size_t)(n * a.H + ih) * W3 + 8 * j) : reinterpret_cast<const bf16_t*>(g_zero_block_c3));
+        }
+        const bf16_t* dyrow = a.dy + (size_t)u * a.OW * K;
+#pragma unroll
+        for (int i = 0; i < DVL; ++i) {
+            const int v = tid + i * NT;
+            rdv[i] = *reinterpret_cast<const u32x4*>(v < a.OW * VPR ? dyrow + (size_t)v * 8
+                                                                   : reinterpret_cast<const bf16_t*>(g_zero_block_c3));
+        }
+    };
+    auto store_row = [&]() {
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            const int v = tid + i * NT;
+            if (v < a.R * a.nvx) {
+                const int r = (int)fdiv((uint32_t)v, a.dNVX), j = v - r * a.nvx;
+                unsigned* dst = reinterpret_cast<unsigned*>(sX + r * a.xrowb + 6 * a.pw + 16 * j);  // 4-byte aligned (pw even)
+                dst[0] = rx[i][0]; dst[1] = rx[i][1]; dst[2] = rx[i][2]; dst[3] = rx[i][3];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < DVL; ++i) {
+            const int v = tid + i * NT;
+            if (v < a.OW * VPR) *reinterpret_cast<u32x4*>(sD + (v / VPR) * DPITCH + (v % VPR) * 16) = rdv[i];
+        }
+    };
+    if ((int)blockIdx.x < a.units) load_row(blockIdx.x);
+    for (int u = blockIdx.x; u < a.units; u += gridDim.x) {
+        store_row();
+        __syncthreads();
+        if (u + (int)gridDim.x < a.units) load_row(u + gridDim.x);
+        for (int step = 0; step < a.nsteps; ++step) {
+            const unsigned char* d0 = sD + (step * 16 + kl) * DPITCH + ccol * 2;
+            bf16x8 fd[FB];
+#pragma unroll
+            for (int b = 0; b < FB; ++b) fd[b] = tr_pair(d0 + b * 64, d0 + 4 * DPITCH + b * 64);
+            const int xs = 6 * a.sw * 16 * step;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (wave + 4 * j < a.NB) {  // uniform per wavefront
+                    const unsigned char* x0 = sX + xo[j] + xs;
+                    const bf16x8 fx = tr_pair(x0, x0 + 6 * a.sw * 4);
+#pragma unroll
+                    for (int b = 0; b < FB; ++b) acc[j][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx, fd[b], acc[j][b], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();  // every wavefront is done with this row before the next one overwrites it
+    }
+
+    // Epilogue.  Accumulator register i holds column (i/4)*8 + half*4 + i%4 of the block for output channel
+    // b*32 + l32; a wavefront-private LDS strip turns that around so that 32 consecutive lanes store 32 consecutive
+    // columns of one output channel (the LDS rows of the main loop are dead after the last barrier).
+    float* outp = a.part + (size_t)blockIdx.x * K * a.Kred;
+    float* red = reinterpret_cast<float*>(smem_s) + wave * (K * 33);
+    const int S3 = a.S * 3;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (wave + 4 * j >= a.NB) continue;
+#pragma unroll
+        for (int b = 0; b < FB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) red[(b * 32 + l32) * 33 + (i >> 2) * 8 + half * 4 + (i & 3)] = acc[j][b][i];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the strip is private to this wavefront
+        const int f = 32 * (wave + 4 * j) + l32;
+        const int r = (int)fdiv((uint32_t)f, a.dSC4), sc = f - r * a.SC4;
+        const bool keep = r < a.R && sc < S3;
+        for (int k = half; k < K; k += 2) {
+            const float v = red[k * 33 + l32];
+            if (keep) outp[(size_t)k * a.Kred + r * S3 + sc] = v;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // strip reads done before the next block overwrites it
+    }
+}
+
+struct C3SPlan {
+    int SC4, NB, xrowb, nsteps;
+    size_t smem;
+};
+bool c3s_plan(const WgradGeom& g, C3SPlan* out) {
+    if (g.C != 3 || (g.K != 32 && g.K != 64)) return false;
+    if ((g.sw % 4) != 0 || (g.pw % 2) != 0 || (g.W % 8) != 0 || g.Q > 64) return false;
+    C3SPlan p;
+    p.SC4 = (g.S * 3 + 3) / 4 * 4;
+    p.NB = (g.R * p.SC4 + 31) / 32;
+    if (p.NB > 16) return false;
+    p.nsteps = (g.Q + 15) / 16;
+    // bytes of one x row in LDS: the row itself behind its left halo, and the farthest transposing read (pixel
+    // 16*nsteps - 1, last chunk of a filter row)
+    const int data = 6 * g.pw + 2 * g.W * 3;
+    const int reach = 6 * g.sw * (16 * p.nsteps - 1) + 2 * p.SC4;
+    p.xrowb = ((data > reach ? data : reach) + 15) / 16 * 16;
+    if (g.R * (g.W * 3 / 8) > 4 * NT) return false;  // the kernel stages at most 4 x vectors per thread
+    p.smem = (size_t)g.R * p.xrowb + (size_t)16 * p.nsteps * (g.K * 2 + 64);
+    const size_t epi = (size_t)4 * g.K * 33 * sizeof(float);  // the epilogue's transposing strips reuse the buffer
+    if (epi > p.smem) p.smem = epi;
+    if (p.smem > 64 * 1024) return false;
+    *out = p;
+    return true;
+}
+
 int c3_grid(long units) {
     long blocks = (units + 3) / 4;
     const long cap = (long)kNumCU * 2;
@@ -402,16 +572,56 @@ int launch_conv_c3_fwd(const GemmGeom& g, const bf16_t* x, const bf16_t* w, cons
 // (A general-filter variant of the weight gradient was tried and dropped: with lanes indexing the columns k, the
 // element-wise gather touches a different cache line per lane, and the generic kernel, which gathers with lanes
 // indexing pixels and transposes through LDS, is faster for the 11x11 stride-4 layer.)
-bool wgrad_c3_supported(const WgradGeom& g) {
+static bool wgrad_c3_special(const WgradGeom& g) {
     return g.C == 3 && g.R == 3 && g.S == 3 && g.sh == 1 && g.sw == 1 && (g.K == 32 || g.K == 64) && (g.Q % 8) == 0 &&
            (long)g.N * g.P * g.Q >= 4096;
 }
-const char* wgrad_c3_kernel_name(const WgradGeom& g) { return g.K == 64 ? "wgrad_c3_kernel<2>" : "wgrad_c3_kernel<1>"; }
+static bool wgrad_c3_strided(const WgradGeom& g) {
+    C3SPlan p;
+    return !wgrad_c3_special(g) && c3s_plan(g, &p) && (long)g.N * g.P >= 64;
+}
+bool wgrad_c3_supported(const WgradGeom& g) { return wgrad_c3_special(g) || wgrad_c3_strided(g); }
+const char* wgrad_c3_kernel_name(const WgradGeom& g) {
+    if (wgrad_c3_strided(g)) return g.K == 64 ? "wgrad_c3_strided_kernel<2>" : "wgrad_c3_strided_kernel<1>";
+    return g.K == 64 ? "wgrad_c3_kernel<2>" : "wgrad_c3_kernel<1>";
+}
 
-int wgrad_c3_nsplit(const WgradGeom& g) { return c3_grid(((long)g.N * g.P * g.Q + 15) / 16); }
+int wgrad_c3_nsplit(const WgradGeom& g) {
+    if (wgrad_c3_strided(g)) {
+        // at least 8 output rows per work-group (each leaves a K x R*S*3 fp32 partial), at most two groups per CU
+        const long units = (long)g.N * g.P, cap = (long)kNumCU * 2;
+        const long want = units / 8;
+        return (int)(want < 1 ? 1 : want < cap ? want : cap);
+    }
+    return c3_grid(((long)g.N * g.P * g.Q + 15) / 16);
+}
 
 int launch_wgrad_c3(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* part, hipStream_t st) {
     if (!wgrad_c3_supported(g)) return set_error(WAP_EINVAL, "internal: 3-channel weight-gradient kernel not applicable");
+    if (wgrad_c3_strided(g)) {
+        C3SPlan p;
+        if (!c3s_plan(g, &p)) return set_error(WAP_EINVAL, "internal: strided 3-channel weight-gradient plan");
+        C3SArgs sa = {};
+        sa.x = x; sa.dy = dy; sa.part = part;
+        sa.N = g.N; sa.H = g.H; sa.W = g.W; sa.OH = g.P; sa.OW = g.Q; sa.R = g.R; sa.S = g.S;
+        sa.sh = g.sh; sa.sw = g.sw; sa.ph = g.ph; sa.pw = g.pw;
+        sa.SC4 = p.SC4; sa.NB = p.NB; sa.Kred = g.R * g.S * 3; sa.xrowb = p.xrowb;
+        sa.units = g.N * g.P; sa.nsteps = p.nsteps; sa.nvx = g.W * 3 / 8;
+        sa.dOH = make_fastdiv((uint32_t)g.P);
+        sa.dSC4 = make_fastdiv((uint32_t)p.SC4);
+        sa.dNVX = make_fastdiv((uint32_t)sa.nvx);
+        static bool attr_done = false;
+        if (!attr_done) {
+            for (const void* f : {(const void*)wgrad_c3_strided_kernel<1>, (const void*)wgrad_c3_strided_kernel<2>}) {
+                hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+                if (e != hipSuccess) return set_error(WAP_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+            }
+            attr_done = true;
+        }
+        if (g.K == 64) hipLaunchKernelGGL(wgrad_c3_strided_kernel<2>, dim3(nsplit), dim3(NT), p.smem, st, sa);
+        else hipLaunchKernelGGL(wgrad_c3_strided_kernel<1>, dim3(nsplit), dim3(NT), p.smem, st, sa);
+        return check_launch("wgrad_c3_strided");
+    }
     C3Args a = {};
     a.x = x;
     a.dy = dy;

@@ -60,6 +60,10 @@ CASES = [
     ("c3_general_5x5_s2_k32", (9, 63, 61, 3, 32, 5, 5, 2, 2), (-1, -1, -1)),
     ("c3_general_11x11_s4_k64", (4, 131, 135, 3, 64, 11, 11, 4, 2), (-1, -1, -1)),
     ("c3_general_7x3_rect_stride_1_3", (3, 20, 40, 3, 64, 7, 3, (1, 3), (3, 0)), (-1, -1, -1)),
+    # 3 input channels, horizontal stride 4: weight gradient from input rows held in LDS (no gather)
+    ("c3_strided_wgrad_11x11_s4_k64", (5, 64, 72, 3, 64, 11, 11, 4, 2), (-1, -1, -1)),
+    ("c3_strided_wgrad_7x7_s4_k32", (6, 50, 96, 3, 32, 7, 7, 4, 2), (-1, -1, -1)),
+    ("c3_strided_wgrad_5x9_rect_stride_2_4_pad_1_0", (8, 30, 64, 3, 64, 5, 9, (2, 4), (1, 0)), (-1, -1, -1)),
 ]
 
 
