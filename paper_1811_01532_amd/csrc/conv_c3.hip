@@ -12,6 +12,10 @@
 //             are gathered; per-work-group partial sums are added by the fixed-order reduce kernel.
 // Reduction index k = (r * 3 + s) * 3 + c; an input row contributes 9 consecutive bf16 (3 pixels x 3
 // channels), so k = r * 9 + j addresses element (ow - pad) * 3 + j of input row oh - pad + r.
+// Larger filters: conv_c3_fwd_general_kernel gathers the same way for any R x S and stride; for a horizontal
+// stride that is a multiple of 4 (the 11x11 stride-4 layer) conv_c3_fwd_strided_kernel and wgrad_c3_strided_kernel
+// keep the R input rows of one output row in LDS, where the im2col rows of neighbouring pixels are overlapping
+// contiguous runs that start 6*stride bytes apart, so no element-wise gather is left.
 // Serves the first "primary" convolution node of Section 3.2.2 (forward and weight-gradient halves of
 // t_c, Eq. 1); its input gradient is never needed.
 #include "wap_internal.h"
@@ -475,6 +479,167 @@ __global__ __launch_bounds__(NT) void wgrad_c3_strided_kernel(const C3SArgs a) {
     }
 }
 
+// ---- forward for the same layers (large filter, horizontal stride a multiple of 4): the R input rows of one
+// output row sit in LDS exactly as above, and the MFMA operand of pixel ow for 8 consecutive reduction columns of
+// filter row r is 16 contiguous, 8-byte aligned bytes at "row base + 6*sw*ow + 2*column": two 8-byte LDS reads
+// instead of eight element-wise global loads.  Columns are numbered r * SC8 + (s*3 + c), SC8 = S*3 rounded up to
+// a multiple of 8; the surplus columns meet zero weights (inputs are assumed finite).  Wavefront (pt, b) owns
+// pixels pt*32.. of the row and the 32-channel block b, with that block's weights in registers as MFMA fragments
+// for the whole kernel; the output row leaves through an LDS tile as contiguous 16-byte stores.
+struct C3FArgs {
+    const bf16_t* x;
+    const bf16_t* w;
+    const float* bias;
+    bf16_t* y;
+    int N, H, W, OH, OW, R, S, sh, sw, ph, pw;
+    int G8, ksteps, Kred, xrowb, units, nvx, relu;  // 8-column groups per filter row, 16-deep reduction steps
+    FastDiv dOH, dNVX, dG8, dKred, dS3;
+};
+constexpr int C3F_KS = 28;  // most reduction steps (weight fragments held in registers)
+
+template <int FB>
+__global__ __launch_bounds__(NT) void conv_c3_fwd_strided_kernel(const C3FArgs a) {
+    constexpr int K = 32 * FB;
+    constexpr int OPITCH = K * 2 + 16;
+    constexpr int VPR = K / 8;
+    extern __shared__ __align__(16) unsigned char smem_f[];
+    unsigned char* sX = smem_f;                 // [R][xrowb]: element e of an input row at byte 6*pw + 2*e
+    unsigned char* sO = smem_f + a.R * a.xrowb;  // [64][OPITCH] output tile
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int pt = wave / FB, b = wave % FB;
+    const bool active = pt * 32 < a.OW;
+    const int S3 = a.S * 3;
+    // Weight fragments: reduction step ks, half h -> column group ks*2 + h -> filter row r, columns sc .. sc + 7.
+    // The work-group first lays all weights out in fragment order in LDS (coalesced reads of w, surplus columns
+    // zero), then every wavefront takes its block's fragments into registers; the area is reused for the rows.
+    {
+        const int nfrag16 = FB * a.ksteps * 64;  // 16-byte fragments
+        for (int i = tid; i < nfrag16; i += NT) *reinterpret_cast<u32x4*>(smem_f + i * 16) = u32x4{0u, 0u, 0u, 0u};
+        __syncthreads();
+        unsigned short* wl = reinterpret_cast<unsigned short*>(smem_f);
+        for (int idx = tid; idx < K * a.Kred; idx += NT) {
+            const int ch = (int)fdiv((uint32_t)idx, a.dKred), k = idx - ch * a.Kred;
+            const int r = (int)fdiv((uint32_t)k, a.dS3), sc = k - r * S3;
+            const int gi = r * a.G8 + (sc >> 3);
+            wl[((((ch >> 5) * a.ksteps + (gi >> 1)) * 64) + (gi & 1) * 32 + (ch & 31)) * 8 + (sc & 7)] = a.w[idx];
+        }
+        __syncthreads();
+    }
+    bf16x8 wf[C3F_KS];
+#pragma unroll
+    for (int ks = 0; ks < C3F_KS; ++ks) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (ks < a.ksteps) v = *reinterpret_cast<const u32x4*>(smem_f + ((b * a.ksteps + ks) * 64 + lane) * 16);
+        wf[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+    __syncthreads();  // every wavefront holds its fragments: the area becomes the row buffer
+    for (int i = tid; i < a.R * a.xrowb / 16; i += NT) *reinterpret_cast<u32x4*>(sX + i * 16) = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
+    const int pixoff = 6 * a.sw * (pt * 32 + l32);
+
+    const int W3 = a.W * 3;
+    constexpr int XV = 4;  // 16-byte x vectors per thread (R * nvx <= 1024)
+    u32x4 rx[XV];
+    auto load_row = [&](int u) {
+        const int n = (int)fdiv((uint32_t)u, a.dOH), oh = u - n * a.OH;
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            const int v = tid + i * NT;
+            const int r = (int)fdiv((uint32_t)v, a.dNVX), j = v - r * a.nvx;
+            const int ih = oh * a.sh - a.ph + r;
+            const bool ok = v < a.R * a.nvx && (unsigned)ih < (unsigned)a.H;
+            rx[i] = *reinterpret_cast<const u32x4*>(
+                ok ? a.x + ((size_t)(n * a.H + ih) * W3 + 8 * j) : reinterpret_cast<const bf16_t*>(g_zero_block_c3));
+        }
+    };
+    if ((int)blockIdx.x < a.units) load_row(blockIdx.x);
+    for (int u = blockIdx.x; u < a.units; u += gridDim.x) {
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            const int v = tid + i * NT;
+            if (v < a.R * a.nvx) {
+                const int r = (int)fdiv((uint32_t)v, a.dNVX), j = v - r * a.nvx;
+                unsigned* dst = reinterpret_cast<unsigned*>(sX + r * a.xrowb + 6 * a.pw + 16 * j);  // 4-byte aligned (pw even)
+                dst[0] = rx[i][0]; dst[1] = rx[i][1]; dst[2] = rx[i][2]; dst[3] = rx[i][3];
+            }
+        }
+        __syncthreads();  // the row is complete; the previous row's output tile has been stored
+        if (u + (int)gridDim.x < a.units) load_row(u + gridDim.x);
+        if (active) {
+            f32x16 acc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+            int r = 0, g8 = half;  // column group of this half-wavefront, kept incrementally (G8 >= 2)
+#pragma unroll
+            for (int ks = 0; ks < C3F_KS; ++ks) {
+                if (ks < a.ksteps) {  // uniform
+                    const int rr = r < a.R ? r : a.R - 1;  // past the filter: any readable row, the weights are zero
+                    const unsigned char* xa = sX + rr * a.xrowb + g8 * 16 + pixoff;
+                    const uint2 lo = *reinterpret_cast<const uint2*>(xa);
+                    const uint2 hi = *reinterpret_cast<const uint2*>(xa + 8);
+                    const u32x4 xv = {lo.x, lo.y, hi.x, hi.y};
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks], __builtin_bit_cast(bf16x8, xv), acc, 0, 0, 0);
+                    g8 += 2;
+                    if (g8 >= a.G8) { g8 -= a.G8; ++r; }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ch = b * 32 + q * 8 + half * 4;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[q * 4 + e];
+                if (a.bias) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += a.bias[ch + e];
+                }
+                if (a.relu) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+                }
+                *reinterpret_cast<uint2*>(sO + (pt * 32 + l32) * OPITCH + ch * 2) =
+                    make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16),
+                               (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+            }
+        }
+        __syncthreads();  // output tile complete, input rows consumed
+        bf16_t* yrow = a.y + (size_t)u * a.OW * K;
+        for (int v = tid; v < a.OW * VPR; v += NT)
+            *reinterpret_cast<u32x4*>(yrow + (size_t)v * 8) =
+                *reinterpret_cast<const u32x4*>(sO + (v / VPR) * OPITCH + (v % VPR) * 16);
+    }
+}
+
+struct C3FPlan {
+    int G8, ksteps, xrowb;
+    size_t smem;
+};
+bool c3f_plan(const GemmGeom& g, C3FPlan* out) {
+    if (g.IC != 3 || (g.Ncols != 32 && g.Ncols != 64) || g.div_h != 1 || g.div_w != 1) return false;
+    if ((g.mul_w % 4) != 0 || (g.pad_w % 2) != 0 || (g.IW % 8) != 0 || g.OW > 64) return false;
+    C3FPlan p;
+    const int SC8 = (g.S * 3 + 7) / 8 * 8;
+    p.G8 = SC8 / 8;
+    if (p.G8 < 2) return false;
+    p.ksteps = (g.R * p.G8 + 1) / 2;
+    if (p.ksteps > C3F_KS) return false;
+    if (g.R * (g.IW * 3 / 8) > 4 * NT) return false;  // the kernel stages at most 4 x vectors per thread
+    const int data = 6 * g.pad_w + 2 * g.IW * 3;
+    const int reach = 6 * g.mul_w * 63 + 2 * SC8;  // pixel 63, last column group of a filter row
+    p.xrowb = ((data > reach ? data : reach) + 15) / 16 * 16;
+    p.smem = (size_t)g.R * p.xrowb + (size_t)64 * (g.Ncols * 2 + 16);
+    const size_t frag = (size_t)(g.Ncols / 32) * p.ksteps * 64 * 16;  // the weight fragments pass through the same area
+    if (frag > p.smem) p.smem = frag;
+    if (p.smem > 64 * 1024) return false;
+    *out = p;
+    return true;
+}
+bool c3_fwd_strided(const GemmGeom& g) {
+    C3FPlan p;
+    return !(g.R == 3 && g.S == 3 && g.mul_h == 1 && g.mul_w == 1) && c3f_plan(g, &p) && g.M / g.OW >= 64;
+}
+
 struct C3SPlan {
     int SC4, NB, xrowb, nsteps;
     size_t smem;
@@ -519,16 +684,47 @@ size_t c3_general_smem(const GemmGeom& g) {
 
 bool conv_c3_fwd_supported(const GemmGeom& g) {
     if (g.IC != 3 || g.div_h != 1 || g.div_w != 1 || (g.Ncols != 32 && g.Ncols != 64)) return false;
-    return c3_special(g) || c3_general_smem(g) <= 64 * 1024;
+    return c3_special(g) || c3_fwd_strided(g) || c3_general_smem(g) <= 64 * 1024;
 }
 const char* conv_c3_fwd_kernel_name(const GemmGeom& g) {
     if (c3_special(g)) return g.Ncols == 64 ? "conv_c3_fwd_kernel<2>" : "conv_c3_fwd_kernel<1>";
+    if (c3_fwd_strided(g)) return g.Ncols == 64 ? "conv_c3_fwd_strided_kernel<2>" : "conv_c3_fwd_strided_kernel<1>";
     return g.Ncols == 64 ? "conv_c3_fwd_general_kernel<2>" : "conv_c3_fwd_general_kernel<1>";
 }
 
 int launch_conv_c3_fwd(const GemmGeom& g, const bf16_t* x, const bf16_t* w, const float* bias, bool relu, bf16_t* y,
                        hipStream_t st) {
     if (!conv_c3_fwd_supported(g)) return set_error(WAP_EINVAL, "internal: 3-channel forward kernel not applicable");
+    if (!c3_special(g) && c3_fwd_strided(g)) {
+        C3FPlan p;
+        if (!c3f_plan(g, &p)) return set_error(WAP_EINVAL, "internal: strided 3-channel forward plan");
+        C3FArgs fa = {};
+        fa.x = x; fa.w = w; fa.bias = bias; fa.y = y;
+        fa.N = g.M / (g.OH * g.OW); fa.H = g.IH; fa.W = g.IW; fa.OH = g.OH; fa.OW = g.OW; fa.R = g.R; fa.S = g.S;
+        fa.sh = g.mul_h; fa.sw = g.mul_w; fa.ph = g.pad_h; fa.pw = g.pad_w;
+        fa.G8 = p.G8; fa.ksteps = p.ksteps; fa.Kred = g.Kred; fa.xrowb = p.xrowb;
+        fa.units = fa.N * g.OH; fa.nvx = g.IW * 3 / 8; fa.relu = relu ? 1 : 0;
+        fa.dOH = make_fastdiv((uint32_t)g.OH);
+        fa.dNVX = make_fastdiv((uint32_t)fa.nvx);
+        fa.dG8 = make_fastdiv((uint32_t)p.G8);
+        fa.dKred = make_fastdiv((uint32_t)g.Kred);
+        fa.dS3 = make_fastdiv((uint32_t)(g.S * 3));
+        static bool attr_done = false;
+        if (!attr_done) {
+            for (const void* f : {(const void*)conv_c3_fwd_strided_kernel<1>, (const void*)conv_c3_fwd_strided_kernel<2>}) {
+                hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+                if (e != hipSuccess) return set_error(WAP_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+            }
+            attr_done = true;
+        }
+        // every wavefront gathers its weight fragments once: long-lived groups, at least 4 output rows each
+        long want = (long)fa.units / 4;
+        const long cap = (long)kNumCU * 2;  // LDS (the fragment staging area) and registers allow two groups per CU
+        const int sgrid = (int)(want < 1 ? 1 : want < cap ? want : cap);
+        if (g.Ncols == 64) hipLaunchKernelGGL(conv_c3_fwd_strided_kernel<2>, dim3(sgrid), dim3(NT), p.smem, st, fa);
+        else hipLaunchKernelGGL(conv_c3_fwd_strided_kernel<1>, dim3(sgrid), dim3(NT), p.smem, st, fa);
+        return check_launch("conv_c3_fwd_strided");
+    }
     C3Args a = {};
     a.x = x;
     a.w = w;
@@ -569,9 +765,9 @@ int launch_conv_c3_fwd(const GemmGeom& g, const bf16_t* x, const bf16_t* w, cons
     return check_launch("conv_c3_fwd");
 }
 
-// (A general-filter variant of the weight gradient was tried and dropped: with lanes indexing the columns k, the
-// element-wise gather touches a different cache line per lane, and the generic kernel, which gathers with lanes
-// indexing pixels and transposes through LDS, is faster for the 11x11 stride-4 layer.)
+// (A gather-based general-filter weight gradient, lanes indexing the columns k, was tried and dropped: every lane
+// touches a different cache line.  Large filters at horizontal stride 4 use the rows-in-LDS kernel above; all other
+// first-layer shapes fall to the generic kernel.)
 static bool wgrad_c3_special(const WgradGeom& g) {
     return g.C == 3 && g.R == 3 && g.S == 3 && g.sh == 1 && g.sw == 1 && (g.K == 32 || g.K == 64) && (g.Q % 8) == 0 &&
            (long)g.N * g.P * g.Q >= 4096;
