@@ -28,6 +28,7 @@ constexpr int BK = 64, NT = 256;
 constexpr int PITCH = (BK + 8) * 2;  // 144 bytes per padded pixel
 constexpr int MAX_PATCH = 352;       // padded pixels (>= (tile h + R - 1) * (tile w + S - 1)); also the staging area
 constexpr int MAX_PATCH_FLAT = 384;  // the same for flat (raster-order) tiles, which may straddle rows and images
+constexpr int MAX_PATCH_FLAT64 = 512;  // flat 192-pixel x 64-channel tiles (5x5 filters on 27-wide maps, across images)
 
 struct TArgs {
     const bf16_t* A;
@@ -89,14 +90,14 @@ __device__ __forceinline__ u32x4 unpool_select8(u32x4 v, u32x2 am, unsigned code
 // TW = 0: flat tiles, 32*FM*PG consecutive output pixels in raster order (they may straddle rows and images;
 // the patch is then a run of the zero-padded image in raster order, as in conv_patch.hip).  UP: pooled input operand.
 template <int FN, int TW, int FM, int PG, bool UP>
-__global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel(const TArgs a) {
+__global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_tile2d_kernel(const TArgs a) {
     constexpr bool FLAT = (TW == 0);
     constexpr int BM = 32 * FM * PG;
     constexpr int CG = 4 / PG;
     constexpr int TWD = FLAT ? 1 : TW;  // divisor that is never zero
     constexpr int TH = BM / TWD;
     static_assert(FLAT || TH * TW == BM, "tile width must divide the tile");
-    constexpr int PATCH_ROWS = FLAT ? MAX_PATCH_FLAT : MAX_PATCH;
+    constexpr int PATCH_ROWS = FLAT ? (PG == 2 ? MAX_PATCH_FLAT64 : MAX_PATCH_FLAT) : MAX_PATCH;
     constexpr int PV = (PATCH_ROWS * 8 + NT - 1) / NT;  // 16-byte patch vectors per thread
     extern __shared__ __align__(16) unsigned char smem[];
     const GemmGeom& g = a.g;
@@ -436,7 +437,7 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 ? 3 : 2)) void conv_tile2d_kernel
 template <int FN, int TW, int FM, int PG, bool UP>
 int launch_tile2d_u(const TArgs& ta, hipStream_t st) {
     auto kfn = conv_tile2d_kernel<FN, TW, FM, PG, UP>;
-    constexpr size_t smem = (size_t)(TW == 0 ? MAX_PATCH_FLAT : MAX_PATCH) * PITCH;
+    constexpr size_t smem = (size_t)(TW == 0 ? (PG == 2 ? MAX_PATCH_FLAT64 : MAX_PATCH_FLAT) : MAX_PATCH) * PITCH;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
@@ -457,10 +458,11 @@ int launch_tile2d_t(const TArgs& ta, hipStream_t st) {
 namespace {
 struct TileCfg {
     int fn, tw, th, variant;  // variant 0: 256 pixels as 2 x 4 fragments; 1: 224 pixels (8 x 28) as 1 x 7 fragments,
-                              // 128 channels; 2: the same with flat tiles (224 consecutive pixels)
+                              // 128 channels; 2: the same with flat tiles (224 consecutive pixels); 3: flat tiles of
+                              // 192 pixels x 64 channels (2 x 3 fragments) for thin outputs on maps no 2-D tile divides
 };
-// largest flat patch (in padded pixels) any 224-pixel raster-order tile of this geometry needs
-int max_flat_patch(const GemmGeom& g) {
+// largest flat patch (in padded pixels) any bm-pixel raster-order tile of this geometry needs
+int max_flat_patch(const GemmGeom& g, int bm) {
     const int PH = g.OH + g.R - 1, PW = g.OW + g.S - 1;
     const long OHW = (long)g.OH * g.OW;
     auto pflat = [&](long m) {
@@ -469,8 +471,8 @@ int max_flat_patch(const GemmGeom& g) {
         return n * PH * PW + oh * PW + ow;
     };
     long worst = 0;
-    for (long m0 = 0; m0 < g.M; m0 += 224) {
-        long ml = (m0 + 224 <= g.M ? m0 + 224 : g.M) - 1;
+    for (long m0 = 0; m0 < g.M; m0 += bm) {
+        long ml = (m0 + bm <= g.M ? m0 + bm : g.M) - 1;
         long len = pflat(ml) + (long)(g.R - 1) * PW + (g.S - 1) + 1 - pflat(m0);
         if (len > worst) worst = len;
     }
@@ -490,8 +492,10 @@ TileCfg tile_cfg(const GemmGeom& g) {
     // maps of 28k x 8j pixels (56 x 56): 8 x 28 tiles, one 224-pixel strip per wavefront, 128-channel tiles
     if ((g.Ncols % 128) == 0 && (g.OW % 28) == 0 && (g.OH % 8) == 0 && (8 + g.R - 1) * (28 + g.S - 1) <= MAX_PATCH)
         c = {1, 28, 8, 1};
-    else if ((g.Ncols % 128) == 0 && g.M >= 224 * 4 && max_flat_patch(g) <= MAX_PATCH_FLAT)
+    else if ((g.Ncols % 128) == 0 && g.M >= 224 * 4 && max_flat_patch(g, 224) <= MAX_PATCH_FLAT)
         c = {1, 0, 0, 2};
+    else if (g.Ncols == 64 && g.M >= 192 * 4 && max_flat_patch(g, 192) <= MAX_PATCH_FLAT64)
+        c = {1, 0, 0, 3};
     return c;
 }
 }  // namespace
@@ -511,6 +515,7 @@ bool tile2d_preferred(const GemmGeom& g) {
     if (!tile2d_supported(g)) return false;
     const TileCfg c = tile_cfg(g);
     if (c.variant == 0) return g.Ncols <= 128;
+    if (c.variant == 3) return (g.M + 191) / 192 >= 48;  // the alternative is the generic tap-by-tap kernel (measured)
     return (long)((g.M + 223) / 224) * (g.Ncols / 128) >= kNumCU * 3 / 4;
 }
 
@@ -519,8 +524,10 @@ const char* tile2d_kernel_name(const GemmGeom& g, bool unpool) {
     const int u = unpool ? 1 : 0;
     static const char* n1[2] = {"conv_tile2d_kernel<1,28,7,1,false>", "conv_tile2d_kernel<1,28,7,1,true>"};
     static const char* n2[2] = {"conv_tile2d_kernel<1,0,7,1,false>", "conv_tile2d_kernel<1,0,7,1,true>"};
+    static const char* n3[2] = {"conv_tile2d_kernel<1,0,3,2,false>", "conv_tile2d_kernel<1,0,3,2,true>"};
     if (c.variant == 1) return n1[u];
     if (c.variant == 2) return n2[u];
+    if (c.variant == 3) return n3[u];
     static const char* names[2][2][3] = {
         {{"conv_tile2d_kernel<1,32,4,2,false>", "conv_tile2d_kernel<1,16,4,2,false>", "conv_tile2d_kernel<1,8,4,2,false>"},
          {"conv_tile2d_kernel<2,32,4,2,false>", "conv_tile2d_kernel<2,16,4,2,false>", "conv_tile2d_kernel<2,8,4,2,false>"}},
@@ -533,7 +540,7 @@ const char* tile2d_kernel_name(const GemmGeom& g, bool unpool) {
 bool tile2d_fuses_unpool(const GemmGeom& g) {
     if (!tile2d_supported(g) || (g.IH % 2) != 0 || (g.IW % 2) != 0) return false;
     const TileCfg c = tile_cfg(g);
-    if (c.variant == 2) return true;
+    if (c.variant >= 2) return true;
     return ((c.th + g.R - 1) / 2 + 1) * ((c.tw + g.S - 1) / 2 + 1) <= 4 * (NT / 8);  // windows per patch: 4 per 8 threads
 }
 
@@ -563,10 +570,11 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
     ta.bias = bias;
     ta.out = out;
     ta.g = g;
-    ta.tiles_n = c.variant >= 1 ? g.Ncols / 128 : g.Ncols / (64 * fn);
-    if (c.variant == 2) {
+    ta.tiles_n = c.variant == 3 ? 1 : c.variant >= 1 ? g.Ncols / 128 : g.Ncols / (64 * fn);
+    if (c.variant >= 2) {
+        const int bm = c.variant == 3 ? 192 : 224;
         ta.tiles_x = ta.tiles_y = ta.tiles_img = 1;
-        ta.tiles_m = (g.M + 223) / 224;
+        ta.tiles_m = (g.M + bm - 1) / bm;
         ta.PH = g.OH + g.R - 1;
         ta.PWp = g.OW + g.S - 1;
         ta.patch_len = 0;  // per tile, computed in the kernel
@@ -593,6 +601,7 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
     ta.dPWp = make_fastdiv((uint32_t)ta.PWp);
     if (c.variant == 1) return launch_tile2d_t<1, 28, 7, 1>(ta, st);
     if (c.variant == 2) return launch_tile2d_t<1, 0, 7, 1>(ta, st);
+    if (c.variant == 3) return launch_tile2d_t<1, 0, 3, 2>(ta, st);
     const int TW = c.tw;
     if (TW == 32) return fn == 1 ? launch_tile2d_t<1, 32, 4, 2>(ta, st) : launch_tile2d_t<2, 32, 4, 2>(ta, st);
     if (TW == 16) return fn == 1 ? launch_tile2d_t<1, 16, 4, 2>(ta, st) : launch_tile2d_t<2, 16, 4, 2>(ta, st);

@@ -44,6 +44,9 @@ CASES = [
     ("tile2d_forced_8x28_strip_tiles_c128_k256", (1, 16, 56, 128, 256, 3, 3, 1, 1), (7, -1, -1)),
     ("tile2d_forced_flat_tiles_w28_ragged", (3, 28, 28, 128, 256, 3, 3, 1, 1), (7, -1, -1)),
     ("tile2d_forced_flat_tiles_w14_straddling_images", (5, 14, 14, 64, 128, 3, 3, 1, 1), (7, -1, -1)),
+    ("tile2d_forced_flat_192x64_tiles_5x5_w27_fwd", (3, 27, 27, 192, 64, 5, 5, 1, 2), (7, -1, -1)),
+    ("tile2d_forced_flat_192x64_tiles_5x5_w27_dgrad", (3, 27, 27, 64, 192, 5, 5, 1, 2), (7, -1, -1)),
+    ("tile2d_forced_flat_192x64_tiles_3x3_w30_even_unpool", (2, 30, 30, 64, 64, 3, 3, 1, 1), (7, -1, -1)),
     # patch-in-LDS weight gradient: masked surplus columns (14 -> 16), a forced uneven split, pad 0
     ("wgrad_patch_w14_masked_columns", (3, 14, 14, 128, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("wgrad_patch_w28_forced_split5", (1, 28, 28, 64, 128, 3, 3, 1, 1), (-1, 3, 5)),
