@@ -132,3 +132,30 @@ def test_profile_argument_checks(wap):
         wap.wap_profile_scratch_bytes(2, d, [8])
     with pytest.raises(wap.WapError):
         wap.wap_profile_layer(0, d, [8], 1, 1, None, 0)
+
+
+def test_pool2x2_backward_entry_points_validate_on_the_host(wap):
+    """Argument checks and the fused / unfused answer of the pooled-gradient backward calls are host logic."""
+    s = 0
+    odd = wap.conv_desc(2, 15, 16, 64, 64, 3, 3, 1, 1)      # 15 x 16 output: no whole 2x2 windows
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_data_pool2x2, odd, 4096, 4096, 4096, None, 4096, None, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_weight_pool2x2, odd, 4096, 4096, 4096, 4096, None, None, s)
+    d = wap.conv_desc(2, 16, 16, 64, 64, 3, 3, 1, 1)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_data_pool2x2, d, None, 4096, 4096, None, 4096, None, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_data_pool2x2, d, 4096, None, 4096, None, 4096, None, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_weight_pool2x2, d, 4096, 4096, 4096 + 8, 4096, None, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_pool2x2_fused, d, wap.WAP_PASS_FWD)
+    # the launch list of the VGG-16 benchmark relies on these answers
+    vgg = {name: wap.conv_desc(64, h, h, c, k, 3, 3, 1, 1)
+           for name, h, c, k in (("conv1_2", 224, 64, 64), ("conv2_2", 112, 128, 128), ("conv3_3", 56, 256, 256),
+                                 ("conv4_3", 28, 512, 512), ("conv5_3", 14, 512, 512))}
+    for name, desc in vgg.items():
+        got = (wap.wap_conv2d_bwd_pool2x2_fused(desc, wap.WAP_PASS_BWD_DATA),
+               wap.wap_conv2d_bwd_pool2x2_fused(desc, wap.WAP_PASS_BWD_WEIGHT))
+        assert got == ((True, True) if name != "conv5_3" else (True, False)), (name, got)
+    # shapes outside the patch kernels: never fused, and the scratch tensor is then required
+    small = wap.conv_desc(4, 32, 32, 3, 16, 3, 3, 1, 1)
+    assert not wap.wap_conv2d_bwd_pool2x2_fused(small, wap.WAP_PASS_BWD_DATA)
+    assert not wap.wap_conv2d_bwd_pool2x2_fused(small, wap.WAP_PASS_BWD_WEIGHT)
+    if wap.wap_conv2d_workspace_bytes(small, wap.WAP_PASS_BWD_DATA) == 0:
+        _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_data_pool2x2, small, 4096, 4096, 4096, None, 4096, None, None, s)
