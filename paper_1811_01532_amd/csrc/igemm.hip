@@ -429,7 +429,9 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
     int nsplit = 1;
     // split the reduction when the tiles alone leave most CUs idle
     if (t < kNumCU * 3 / 4 && ktiles >= 8) {
-        long want = (2L * kNumCU + t - 1) / t;
+        // about one work-group per CU in all (measured on the FC head: more splits only add partial-tile traffic and a
+        // longer epilogue), at least 4 reduction tiles per split
+        long want = kNumCU / t;
         long maxs = ktiles / 4;
         nsplit = (int)(want < maxs ? want : maxs);
         if (nsplit < 1) nsplit = 1;
