@@ -481,10 +481,11 @@ int max_flat_patch(const GemmGeom& g, int bm) {
 // Tile shape for this geometry (width must divide the map, patch must fit), fn = 0 if none.
 TileCfg tile_cfg(const GemmGeom& g) {
     TileCfg c = {0, 0, 0, 0};
-    if (g.Ncols != 64 && (g.Ncols % 128) != 0) return c;
+    if ((g.Ncols % 64) != 0) return c;
+    const bool tiles128 = g.Ncols == 64 || (g.Ncols % 128) == 0;  // 2-D tiles: 64 channels, or 128-channel tiles
     for (int tw : {32, 16, 8}) {
         const int th = 256 / tw;
-        if ((g.OH % th) == 0 && (g.OW % tw) == 0 && (th + g.R - 1) * (tw + g.S - 1) <= MAX_PATCH) {
+        if (tiles128 && (g.OH % th) == 0 && (g.OW % tw) == 0 && (th + g.R - 1) * (tw + g.S - 1) <= MAX_PATCH) {
             c = {g.Ncols == 64 ? 1 : 2, tw, th, 0};
             return c;
         }
@@ -494,8 +495,11 @@ TileCfg tile_cfg(const GemmGeom& g) {
         c = {1, 28, 8, 1};
     else if ((g.Ncols % 128) == 0 && g.M >= 224 * 4 && max_flat_patch(g, 224) <= MAX_PATCH_FLAT)
         c = {1, 0, 0, 2};
-    else if (g.Ncols == 64 && g.M >= 192 * 4 && max_flat_patch(g, 192) <= MAX_PATCH_FLAT64)
-        c = {1, 0, 0, 3};
+    // 192-pixel x 64-channel flat tiles where none of the above applies: 64 or 192 output channels on maps no 2-D
+    // tile divides.  (Tried and dropped for wide outputs at a small minibatch, where the 128-channel tiles leave CUs
+    // idle: with 512 input channels one tile's serial reduction loop alone takes 55 us, longer than the generic
+    // kernel with a split reduction.)
+    if (c.fn == 0 && g.M >= 192 * 4 && max_flat_patch(g, 192) <= MAX_PATCH_FLAT64) c = {1, 0, 0, 3};
     return c;
 }
 }  // namespace
@@ -515,7 +519,10 @@ bool tile2d_preferred(const GemmGeom& g) {
     if (!tile2d_supported(g)) return false;
     const TileCfg c = tile_cfg(g);
     if (c.variant == 0) return g.Ncols <= 128;
-    if (c.variant == 3) return (g.M + 191) / 192 >= 48;  // the alternative is the generic tap-by-tap kernel (measured)
+    if (c.variant == 3) {  // measured against the generic tap-by-tap kernel (64 channels) and conv_patch (wider)
+        const long t3 = (long)((g.M + 191) / 192) * (g.Ncols / 64);
+        return g.Ncols == 64 ? t3 >= 48 : t3 >= 200;
+    }
     return (long)((g.M + 223) / 224) * (g.Ncols / 128) >= kNumCU * 3 / 4;
 }
 
@@ -570,7 +577,7 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
     ta.bias = bias;
     ta.out = out;
     ta.g = g;
-    ta.tiles_n = c.variant == 3 ? 1 : c.variant >= 1 ? g.Ncols / 128 : g.Ncols / (64 * fn);
+    ta.tiles_n = c.variant == 3 ? g.Ncols / 64 : c.variant >= 1 ? g.Ncols / 128 : g.Ncols / (64 * fn);
     if (c.variant >= 2) {
         const int bm = c.variant == 3 ? 192 : 224;
         ta.tiles_x = ta.tiles_y = ta.tiles_img = 1;
