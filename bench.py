@@ -160,6 +160,8 @@ def main():
     ap.add_argument("--minibatch", type=int, default=64)
     ap.add_argument("--no-table", action="store_true", help="skip the minibatch sweep and per-layer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--bias", action="store_true",
+                    help="give every layer a bias (forward add, bias gradient, SGD); the headline runs without")
     ap.add_argument("--link-gbs", type=float, default=76.8,
                     help="one-direction bandwidth of one xGMI link, GB/s (analytic t_s of the workload analysis)")
     ap.add_argument("--link-latency-us", type=float, default=10.0, help="latency of one ring step, microseconds")
@@ -182,7 +184,7 @@ def main():
     torch.cuda.set_device(0)
     net, B, image = a.net, a.minibatch, 224
 
-    plan = wap.StepPlan(net, B, lr=LR, image=image)
+    plan = wap.StepPlan(net, B, lr=LR, image=image, flags=wap.WAP_STEP_BIAS if a.bias else 0)
     buf = _arena(plan, torch)
     init_step(plan, buf, net, B, image, torch, wap, "numpy")
     ops = plan.ops()
@@ -280,7 +282,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{net} full training step (conv+FC fwd/bwd, ReLU, max-pool, softmax-CE, SGD "
                                f"lr={LR}), per-GPU minibatch {B}, 3x{image}x{image} input, 1000 classes",
-                   "net": net, "minibatch": B, "step_gflop": flops_step / 1e9, "ops_per_step": len(ops)},
+                   "net": net, "minibatch": B, "bias": bool(a.bias), "step_gflop": flops_step / 1e9, "ops_per_step": len(ops)},
         "frac_of_bf16_peak": value / PEAK_BF16,
         "images_per_s": B / (ms_per_step * 1e-3),
         "loss_after": loss,

@@ -244,7 +244,14 @@ int wap_choose_gpus(int32_t n_layers, int32_t max_gpus, const double* t_c, const
 typedef struct wap_step_plan wap_step_plan;
 
 /* net: "alexnet" or "vgg16" (layer lists of Section 4.1's two networks, 224x224x3 inputs,
- * 1000 classes, no bias).  The plan is host memory only. */
+ * 1000 classes).  The plan is host memory only.
+ * flags: WAP_STEP_KEEP_GRADS keeps every intermediate gradient in a tensor of its own and every operation
+ * unfused (for inspection); WAP_STEP_BIAS gives every conv / FC layer an fp32 bias (tensors "<layer>.b32",
+ * gradient "<layer>.db"): added in the forward epilogues, its gradient (column sums of the gradient w.r.t. the
+ * layer's pre-activation output) computed by one extra operation per layer, updated by the same SGD launch.
+ * Without the flag the layers have no bias, which is how the benchmark runs. */
+#define WAP_STEP_KEEP_GRADS 1u
+#define WAP_STEP_BIAS 2u
 int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, float lr, uint32_t flags,
                          wap_step_plan** out);
 void wap_step_plan_destroy(wap_step_plan* p);

@@ -122,8 +122,9 @@ __global__ __launch_bounds__(256) void reduce_f32_grouped_kernel(const float* __
     }
 }
 
-// ---- bias gradient, first stage: column sums of a chunk of rows.  A thread owns one 8-channel vector (or one
-// channel) and every RP-th row of the chunk; the RP partial sums per column are then added in thread order. ----
+// ---- bias gradient, first stage: column sums of a chunk of rows (blockIdx.x) for a block of up to 256 column
+// vectors (blockIdx.y).  A thread owns one 8-channel vector (or one channel) and every RP-th row of the chunk; the
+// RP partial sums per column are then added in thread order. ----
 template <int VEC>
 __global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict__ dy, float* __restrict__ part,
                                                         size_t rows, int cols, size_t rows_per_chunk) {
@@ -135,8 +136,8 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict
     const size_t r0 = (size_t)blockIdx.x * rows_per_chunk;
     size_t r1 = r0 + rows_per_chunk;
     if (r1 > rows) r1 = rows;
-    for (int v0 = 0; v0 < cv; v0 += vpb) {
-        const int v = v0 + vec;
+    {
+        const int v = blockIdx.y * vpb + vec;
         float s[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s[e] = 0.f;
@@ -438,10 +439,17 @@ int launch_fill_bf16(bf16_t* p, size_t n, uint32_t seed, hipStream_t st) {
     return check_launch("fill");
 }
 
+// Row chunks of the first stage: about 32 loads per thread (a work-group covers min(vectors per row, 256) vectors side
+// by side and 256 / that many rows per pass), at most ~8 work-groups per CU over all column blocks.
 int bias_grad_chunks(size_t rows, int cols) {
-    (void)cols;
-    size_t chunks = (rows + 255) / 256;  // at least 256 rows per chunk
-    const size_t cap = (size_t)kNumCU * 4;
+    const int vecw = (cols & 7) == 0 ? 8 : 1;
+    const int cv = (cols + vecw - 1) / vecw;
+    const int vpb = cv < 256 ? cv : 256;
+    const int rp = 256 / vpb;
+    const int colblocks = (cv + vpb - 1) / vpb;
+    size_t chunks = (rows + (size_t)32 * rp - 1) / ((size_t)32 * rp);
+    size_t cap = (size_t)kNumCU * 8 / colblocks;
+    if (cap < 1) cap = 1;
     if (chunks > cap) chunks = cap;
     return (int)(chunks < 1 ? 1 : chunks);
 }
@@ -449,10 +457,13 @@ int bias_grad_chunks(size_t rows, int cols) {
 int launch_bias_grad(size_t rows, int cols, const bf16_t* dy, float* db, float* part, hipStream_t st) {
     const int chunks = bias_grad_chunks(rows, cols);
     const size_t rpc = (rows + chunks - 1) / chunks;
-    if ((cols & 7) == 0)
-        hipLaunchKernelGGL(bias_grad_kernel<8>, dim3(chunks), dim3(256), 0, st, dy, part, rows, cols, rpc);
+    const int vecw = (cols & 7) == 0 ? 8 : 1;
+    const int cv = (cols + vecw - 1) / vecw;
+    const int colblocks = (cv + 255) / 256;  // the kernel covers min(cv, 256) vectors per work-group
+    if (vecw == 8)
+        hipLaunchKernelGGL(bias_grad_kernel<8>, dim3(chunks, colblocks), dim3(256), 0, st, dy, part, rows, cols, rpc);
     else
-        hipLaunchKernelGGL(bias_grad_kernel<1>, dim3(chunks), dim3(256), 0, st, dy, part, rows, cols, rpc);
+        hipLaunchKernelGGL(bias_grad_kernel<1>, dim3(chunks, colblocks), dim3(256), 0, st, dy, part, rows, cols, rpc);
     int rc = check_launch("bias_grad");
     if (rc != WAP_OK) return rc;
     return launch_reduce_f32(part, chunks, (size_t)cols, db, st);

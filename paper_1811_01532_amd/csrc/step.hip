@@ -15,7 +15,7 @@ namespace {
 
 enum OpKind {
     OP_PACK, OP_CONV_FWD, OP_POOL_FWD, OP_FC_FWD, OP_SOFTMAX, OP_RELU_BWD, OP_POOL_BWD,
-    OP_FC_DX, OP_FC_DW, OP_CONV_WGRAD, OP_CONV_DGRAD, OP_SGD
+    OP_FC_DX, OP_FC_DW, OP_CONV_WGRAD, OP_CONV_DGRAD, OP_SGD, OP_BIAS_GRAD
 };
 
 struct Tensor {
@@ -35,6 +35,8 @@ struct Op {
     bool prepacked = false;  // weights of this operation are repacked once per step by the OP_PACK operation (copy at t4)
     size_t t0 = 0, t1 = 0, t2 = 0, t3 = 0, t4 = 0, t5 = 0;  // arena offsets, meaning per kind
     bool has_pool = false;  // conv forward whose epilogue also emits the 2x2 max-pool (y_pool at t3, argmax at t5)
+    bool has_bias = false;  // forward operation with an fp32 bias vector (at tb)
+    size_t tb = 0;
     bool unpool = false;    // conv backward whose dy operand is the gradient of the 2x2-pooled output, routed through the
                             // argmax by the kernel's loader (argmax at t5 for the data gradient, t3 for the weight gradient)
     int N = 0, H = 0, W = 0, C = 0, win = 0, st = 0;  // pooling / softmax shapes
@@ -113,7 +115,7 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
         case OP_CONV_DGRAD:
         case OP_FC_DX:
             return launch_fwd_like(op.gg, op.b_tr, op.gp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
-                                   nullptr, op.relu, op.has_pool ? nullptr : (bf16_t*)(base + op.t2), ws, st, ev_mid,
+                                   op.has_bias ? (const float*)(base + op.tb) : nullptr, op.relu, op.has_pool ? nullptr : (bf16_t*)(base + op.t2), ws, st, ev_mid,
                                    op.has_mask ? (const bf16_t*)(base + op.t3) : nullptr, ev_packed,
                                    op.prepacked ? (const void*)(base + op.t4) : nullptr,
                                    op.has_pool ? (bf16_t*)(base + op.t3) : nullptr,
@@ -137,6 +139,8 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
         case OP_SOFTMAX:
             return launch_softmax_xent(op.N, op.C, (const bf16_t*)(base + op.t0), (const int32_t*)(base + op.t1),
                                        (float*)(base + op.t2), (float*)(base + op.t3), (bf16_t*)(base + op.t4), st);
+        case OP_BIAS_GRAD:
+            return launch_bias_grad(op.n, op.C, (const bf16_t*)(base + op.t0), (float*)(base + op.t1), (float*)ws, st);
         case OP_SGD:
             return launch_sgd(op.n, (float*)(base + op.t0), (const float*)(base + op.t1), p->lr,
                               (bf16_t*)(base + op.t2), st);
@@ -152,13 +156,14 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
                          wap_step_plan** out) {
     if (!net || !out) return set_error(WAP_EINVAL, "step plan: NULL argument");
     if (minibatch < 1 || image < 1) return set_error(WAP_EINVAL, "step plan: minibatch and image must be >= 1");
-    if (flags & ~1u) return set_error(WAP_EINVAL, "step plan: unknown flag bits 0x%x", flags);
+    if (flags & ~3u) return set_error(WAP_EINVAL, "step plan: unknown flag bits 0x%x", flags);
     const ConvL* convs;
     int nconv;
     if (!strcmp(net, "alexnet")) { convs = kAlexConvs; nconv = 5; }
     else if (!strcmp(net, "vgg16")) { convs = kVggConvs; nconv = 13; }
     else return set_error(WAP_EINVAL, "step plan: unknown net '%s' (alexnet, vgg16)", net);
-    const bool keep = (flags & 1u) != 0;
+    const bool keep = (flags & WAP_STEP_KEEP_GRADS) != 0;
+    const bool with_bias = (flags & WAP_STEP_BIAS) != 0;
     const int B = minibatch;
 
     // ---- walk the geometry, validating every layer ----
@@ -204,6 +209,14 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         pcount[i] = cnt;
         np += align_up(cnt, 64);
     }
+    // biases (optional) follow the weights in the same three blocks, so the one SGD launch covers them
+    std::vector<size_t> boff(nconv + 3, 0), bcount(nconv + 3, 0);
+    if (with_bias)
+        for (int i = 0; i < nconv + 3; ++i) {
+            boff[i] = np;
+            bcount[i] = i < nconv ? (size_t)convs[i].K : (size_t)fds[i - nconv].out_features;
+            np += align_up(bcount[i], 64);
+        }
     p->n_params = np;
     p->w32_off = p->add("params.w32", np * 4);
     p->dw_off = p->add("params.dw", np * 4);
@@ -213,6 +226,10 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         p->tensors.push_back({lname(i) + ".w32", p->w32_off + poff[i] * 4, pcount[i] * 4});
         p->tensors.push_back({lname(i) + ".dw", p->dw_off + poff[i] * 4, pcount[i] * 4});
         p->tensors.push_back({lname(i) + ".w", p->wb_off + poff[i] * 2, pcount[i] * 2});
+        if (with_bias) {
+            p->tensors.push_back({lname(i) + ".b32", p->w32_off + boff[i] * 4, bcount[i] * 4});
+            p->tensors.push_back({lname(i) + ".db", p->dw_off + boff[i] * 4, bcount[i] * 4});
+        }
     }
 
     // ---- activations ----
@@ -271,6 +288,25 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         }
         p->ops.push_back(op);
     };
+    // gradient of layer `li`'s bias: column sums of the gradient w.r.t. its pre-activation output (rows x cols, bf16)
+    auto push_bias_grad = [&](int li, size_t rows, size_t dy) {
+        if (!with_bias) return;
+        Op op;
+        op.kind = OP_BIAS_GRAD; op.name = lname(li) + ".bias_grad";
+        op.n = rows; op.C = (int)bcount[li];
+        op.t0 = dy; op.t1 = p->dw_off + boff[li] * 4;
+        op.kernel = "bias_grad_kernel";
+        op.bytes = 2.0 * rows * bcount[li] + 4.0 * bcount[li];
+        size_t need = (size_t)bias_grad_chunks(rows, op.C) * op.C * sizeof(float);
+        if (need > ws_need) ws_need = need;
+        p->ops.push_back(op);
+    };
+    auto set_bias = [&](int li) {
+        if (!with_bias) return;
+        Op& f = p->ops.back();
+        f.has_bias = true;
+        f.tb = p->w32_off + boff[li] * 4;
+    };
     auto push_wgrad = [&](OpKind kind, const std::string& name, const WgradGeom& g, size_t x, size_t dy, size_t dw) {
         Op op;
         op.kind = kind; op.name = name; op.wg = g;
@@ -290,6 +326,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         const wap_conv_desc& d = cds[i];
         GemmGeom g = geom_conv_fwd(d);
         push_fwd_like(OP_CONV_FWD, lname(i) + ".fwd", g, false, true, cur, p->wb_off + poff[i] * 2, conv_y[i]);
+        set_bias(i);
         double f = 2.0 * g.M * (double)g.Ncols * g.Kred;
         flops += (i == 0 ? 2.0 : 3.0) * f;
         cur = conv_y[i];
@@ -321,6 +358,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         GemmGeom g = geom_fc_fwd(fds[i]);
         push_fwd_like(OP_FC_FWD, lname(nconv + i) + ".fwd", g, false, kFcs[i].relu, cur, p->wb_off + poff[nconv + i] * 2,
                       fc_y[i]);
+        set_bias(nconv + i);
         flops += 3.0 * 2.0 * B * (double)fds[i].in_features * fds[i].out_features;
         cur = fc_y[i];
     }
@@ -354,6 +392,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             g_cur = op.t2;
         }
         push_wgrad(OP_FC_DW, nm + ".dW", geom_fc_dw(fds[i]), fc_in[i], g_cur, p->dw_off + poff[nconv + i] * 4);
+        push_bias_grad(nconv + i, (size_t)B, g_cur);
         if (!keep) gsel = (g_cur == gbuf[0]) ? 1 : 0;
         std::string in_name = i > 0 ? "g." + lname(nconv + i - 1) + ".y"
                                     : "g." + lname(nconv - 1) + (convs[nconv - 1].pool_win ? ".pool.y" : ".y");
@@ -417,6 +456,8 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             wgop.kernel = wgrad_kernel_name(wgop.wg, wgop.wp, true);
             wgop.bytes += 3.0 * pool_y_elems[i] - 2.0 * conv_y_elems[i];
         }
+        // routing a pooled gradient to the argmax pixels keeps every column's sum: the pooled tensor serves as well
+        push_bias_grad(i, (unpool ? pool_y_elems[i] : conv_y_elems[i]) / d.K, g_cur);
         if (i > 0) {  // the gradient w.r.t. the input image is not needed
             if (!keep) gsel = (g_cur == gbuf[0]) ? 1 : 0;
             std::string in_name = "g." + lname(i - 1) + (convs[i - 1].pool_win ? ".pool.y" : ".y");

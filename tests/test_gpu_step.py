@@ -62,6 +62,12 @@ def _setup(net, B, image, flags, seed_cfg):
     for name, wb in weights.items():
         ar.put_f32(name + ".w32", orc.bf16_bits_to_f64(wb).astype(np.float32))
         ar.put_bf16(name + ".w", wb)
+    # optional fp32 biases, stored under "<layer>#bias" next to the weights
+    if flags & wap.WAP_STEP_BIAS:
+        for j, name in enumerate(list(weights.keys())):
+            b = (0.1 * si.rng(seed_cfg, 70 + j).standard_normal(weights[name].shape[0])).astype(np.float32)
+            weights[name + "#bias"] = b
+            ar.put_f32(name + ".b32", b)
     xb = si.normal_bf16(si.rng(seed_cfg, 0), (B, image, image, 3))
     labels = si.labels(si.rng(seed_cfg, 1), B)
     ar.put_bf16("input", xb)
@@ -69,15 +75,28 @@ def _setup(net, B, image, flags, seed_cfg):
     return plan, ar, shapes, fc_dims, weights, xb, labels
 
 
-@pytest.mark.parametrize("net,B,image", [("vgg16", 2, 32), ("alexnet", 3, 67)])
-def test_step_every_operation_matches_oracle(orc, net, B, image):
+@pytest.mark.parametrize("net,B,image,with_bias", [("vgg16", 2, 32, False), ("alexnet", 3, 67, False),
+                                                    ("vgg16", 2, 32, True), ("alexnet", 3, 67, True)])
+def test_step_every_operation_matches_oracle(orc, net, B, image, with_bias):
     import paper_1811_01532_amd as wap
-    plan, ar, shapes, fc_dims, weights, xb, labels = _setup(net, B, image, wap.WAP_STEP_KEEP_GRADS, 500)
-    print(f"[case] step {net} B={B} image={image} ops={plan.num_ops()}", flush=True)
+    flags = wap.WAP_STEP_KEEP_GRADS | (wap.WAP_STEP_BIAS if with_bias else 0)
+    plan, ar, shapes, fc_dims, weights, xb, labels = _setup(net, B, image, flags, 500)
+    print(f"[case] step {net} B={B} image={image} bias={with_bias} ops={plan.num_ops()}", flush=True)
     plan.run(ar.buf)
     torch.cuda.synchronize()
     f64 = orc.bf16_bits_to_f64
+    biases = {k[:-5]: v.astype(np.float64) for k, v in weights.items() if k.endswith("#bias")}
+    weights = {k: v for k, v in weights.items() if not k.endswith("#bias")}
     w64 = {k: f64(v) for k, v in weights.items()}
+
+    def check_db(L, g_pre):
+        """bias gradient of layer L against the column sums of the device's own pre-activation gradient"""
+        if not with_bias:
+            return
+        K = g_pre.shape[-1]
+        db = gu.host_f64(ar.f32(L + ".db", (K,)))
+        e = gu.rel_err(db, orc.bias_grad(g_pre))
+        assert e <= gu.TOL_F32_OUT, f"{L}.bias_grad rel err {e}"
 
     def check_bf16(name, got_t, ref, tol=gu.TOL_BF16_OUT):
         e = gu.rel_err(gu.host_f64(got_t), ref)
@@ -89,7 +108,7 @@ def test_step_every_operation_matches_oracle(orc, net, B, image):
     for d in shapes:
         L = d["name"]
         y = ar.bf16(L + ".y", (B, d["P"], d["Q"], d["K"]))
-        ref = orc.conv2d_fwd(cur, w64[L], (d["stride"],) * 2, (d["pad"],) * 2, relu=True)
+        ref = orc.conv2d_fwd(cur, w64[L], (d["stride"],) * 2, (d["pad"],) * 2, bias=biases.get(L), relu=True)
         check_bf16(L + ".fwd", y, ref)
         acts[L + ".in"] = cur
         cur = gu.host_f64(y)
@@ -108,7 +127,7 @@ def test_step_every_operation_matches_oracle(orc, net, B, image):
     cur = cur.reshape(B, -1)
     for (name, n_in, n_out, relu) in fc_dims:
         y = ar.bf16(name + ".y", (B, n_out))
-        ref = orc.fc_fwd(cur, w64[name], relu=relu)
+        ref = orc.fc_fwd(cur, w64[name], bias=biases.get(name), relu=relu)
         check_bf16(name + ".fwd", y, ref)
         acts[name + ".in"] = cur
         cur = gu.host_f64(y)
@@ -133,6 +152,7 @@ def test_step_every_operation_matches_oracle(orc, net, B, image):
         dW = ar.f32(name + ".dw", (n_out, n_in))
         e = gu.rel_err(gu.host_f64(dW), orc.fc_bwd_weight(g, acts[name + ".in"]))
         assert e <= gu.TOL_F32_OUT, f"{name}.dW rel err {e}"
+        check_db(name, g)
         in_name = "g." + (fc_dims[idx - 1][0] + ".y" if idx > 0 else last_out)
         gi_t = ar.bf16(in_name, (B, n_in))
         check_bf16(name + ".dx", gi_t, orc.fc_bwd_data(g, w64[name]))
@@ -158,6 +178,7 @@ def test_step_every_operation_matches_oracle(orc, net, B, image):
                                       (d["stride"],) * 2, (d["pad"],) * 2)
         e = gu.rel_err(gu.host_f64(dw), refdw)
         assert e <= gu.TOL_F32_OUT, f"{L}.wgrad rel err {e}"
+        check_db(L, g)
         if i > 0:
             prev = shapes[i - 1]
             in_name = "g." + prev["name"] + (".pool.y" if prev["pool"] else ".y")
@@ -175,28 +196,52 @@ def test_step_every_operation_matches_oracle(orc, net, B, image):
         assert np.max(np.abs(w_after - ref)) <= 2.0 ** -22 * max(1e-30, np.max(np.abs(ref))), name + ".sgd"
         wb_after = gu.host_f64(ar.bf16(name + ".w", shape))
         assert np.array_equal(wb_after, orc.round_bf16(w_after)), name + ".w bf16 copy"
+    for name, b in biases.items():
+        db = gu.host_f64(ar.f32(name + ".db", b.shape))
+        b_after = gu.host_f64(ar.f32(name + ".b32", b.shape))
+        ref = orc.sgd(b, db, float(np.float32(LR)))
+        assert np.max(np.abs(b_after - ref)) <= 2.0 ** -22 * max(1e-30, np.max(np.abs(ref))), name + ".b32 sgd"
 
 
-@pytest.mark.parametrize("net,B,image", [("vgg16", 2, 32), ("vgg16", 1, 256), ("alexnet", 3, 67), ("alexnet", 2, 224)])
-def test_step_without_kept_gradients_is_bitwise_the_same(orc, net, B, image):
+@pytest.mark.parametrize("net,B,image,extra", [("vgg16", 2, 32, 0), ("vgg16", 1, 256, 0), ("alexnet", 3, 67, 0),
+                                                ("alexnet", 2, 224, 0), ("vgg16", 2, 64, 2), ("alexnet", 2, 131, 2)])
+def test_step_without_kept_gradients_is_bitwise_the_same(orc, net, B, image, extra):
     """The production plan (ping-pong gradient buffers, pool taken in the conv epilogue, pool backward routed in the
     backward kernels' loaders, ReLU derivatives riding on data-gradient epilogues) gives the same gradients and loss
     as the plan that keeps every intermediate, which the teacher-forced test checks against the oracle.  The larger
-    images reach the fused paths the 32-pixel case is too small for (also the FC data gradient that carries the
-    mask of the last pooled layer)."""
+    images reach the fused paths the 32-pixel case is too small for.  With biases the bias gradient of a layer whose
+    pool backward is routed in the loaders is summed over the pooled gradient instead of the full-size one: the same
+    sum in another order, so after the first step those vectors agree to fp32 rounding and everything else bit for
+    bit (the second step then starts from biases that differ in the last bits)."""
     import paper_1811_01532_amd as wap
     res = []
-    for flags in (wap.WAP_STEP_KEEP_GRADS, 0):
+    steps = 1 if extra else 2
+    for flags in (wap.WAP_STEP_KEEP_GRADS | extra, extra):  # extra = 2: with biases
         plan, ar, shapes, fc_dims, weights, _, _ = _setup(net, B, image, flags, 501)
-        print(f"[case] step {net} B={B} image={image} flags={flags} ops={[o[0] for o in plan.ops()] if flags == 0 else plan.num_ops()}", flush=True)
-        plan.run(ar.buf)
-        plan.run(ar.buf)   # a second step on the updated weights
+        print(f"[case] step {net} B={B} image={image} flags={flags} ops={[o[0] for o in plan.ops()] if not (flags & 1) else plan.num_ops()}", flush=True)
+        for _ in range(steps):  # without biases: a second step on the updated weights
+            plan.run(ar.buf)
         torch.cuda.synchronize()
+        names = [k for k in weights if not k.endswith("#bias")]
+        nw = sum(ar.t[k + ".dw"][1] for k in names) // 4   # the weights come first in the parameter blocks
         n = ar.t["params.dw"][1] // 4
         res.append((ar.f32("params.dw", (n,)).clone(), ar.f32("params.w32", (n,)).clone(),
-                    ar.f32("loss", (4,))[0].item()))
-    assert torch.equal(res[0][0], res[1][0])
-    assert torch.equal(res[0][1], res[1][1])
+                    ar.f32("loss", (4,))[0].item(), nw,
+                    {k: ar.f32(k + ".db", (weights[k].shape[0],)).clone() for k in names} if extra else {}))
+    nw = res[0][3]
+    assert nw <= res[0][0].numel() and (extra or nw > 0)
+    if not extra:
+        assert torch.equal(res[0][0], res[1][0])
+        assert torch.equal(res[0][1], res[1][1])
+    else:
+        # weight gradients (the leading part of the block, alignment gaps included) bit for bit, bias gradients close
+        last_w = max(ar.t[k + ".dw"][0] + ar.t[k + ".dw"][1] for k in names) - ar.t["params.dw"][0]
+        assert torch.equal(res[0][0][:last_w // 4], res[1][0][:last_w // 4])
+        assert torch.equal(res[0][1][:last_w // 4], res[1][1][:last_w // 4])
+        for k in names:
+            a, b = res[0][4][k].double(), res[1][4][k].double()
+            scale = max(float(a.abs().max()), 1e-30)
+            assert float((a - b).abs().max()) <= 1e-5 * scale, f"{k}.db differs by more than fp32 summation order"
     assert res[0][2] == res[1][2]
     assert np.isfinite(res[0][2])
 
