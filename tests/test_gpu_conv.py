@@ -56,6 +56,8 @@ CASES = [
     # backward through a 2x2 pool routed in the loaders: flat data-gradient tiles, two dy blocks per wavefront
     ("unpool_flat_w14_c128_k128", (5, 14, 14, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
     ("unpool_w112_c64_k128", (1, 32, 112, 64, 128, 3, 3, 1, 1), (-1, -1, -1)),
+    ("unpool_5x5_flat_tiles_c64_k64", (2, 32, 32, 64, 64, 5, 5, 1, 2), (7, -1, -1)),
+    ("unpool_1x3_filter_2d_tiles_c64_k64", (2, 16, 64, 64, 64, 1, 3, 1, (0, 1)), (7, -1, -1)),
     # 3-input-channel first-layer kernels: ragged last tile / step, 32 and 64 output channels, pad 0
     ("c3_k64_ragged", (3, 41, 40, 3, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("c3_k32", (2, 48, 48, 3, 32, 3, 3, 1, 1), (-1, -1, -1)),
