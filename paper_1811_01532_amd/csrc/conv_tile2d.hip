@@ -478,6 +478,20 @@ int max_flat_patch(const GemmGeom& g, int bm) {
     }
     return (int)worst;
 }
+// Wide outputs at a small minibatch: the 128-channel tiles leave most CUs without work and conv_patch.hip does not
+// apply, so the alternative is the generic tap-by-tap kernel with a split reduction (measured ~380 TFLOP/s there).
+// One 192 x 64 tile's serial reduction loop takes ~6.6 us per 64-channel slice of a 3x3 filter whatever the
+// minibatch, so the flat tiles win only once the layer holds enough work.
+bool flat64_wins_small_batch(const GemmGeom& g) {
+    if ((g.Ncols % 64) != 0 || g.Ncols <= 64 || g.M >= 224 * 32 || g.M < 192 * 4) return false;
+    if ((long)((g.M + 191) / 192) * (g.Ncols / 64) < 64) return false;
+    if (max_flat_patch(g, 192) > MAX_PATCH_FLAT64) return false;
+    const double flops = 2.0 * g.M * (double)g.Ncols * g.Kred;
+    const double t_generic = flops / 380e12;
+    const double floor_s = 6.6e-6 * (g.IC / 64) * (g.R * g.S / 9.0);
+    const double t_flat = floor_s > flops / 900e12 ? floor_s : flops / 900e12;
+    return t_flat < 0.85 * t_generic;
+}
 // Tile shape for this geometry (width must divide the map, patch must fit), fn = 0 if none.
 TileCfg tile_cfg(const GemmGeom& g) {
     TileCfg c = {0, 0, 0, 0};
@@ -495,11 +509,12 @@ TileCfg tile_cfg(const GemmGeom& g) {
         c = {1, 28, 8, 1};
     else if ((g.Ncols % 128) == 0 && g.M >= 224 * 4 && max_flat_patch(g, 224) <= MAX_PATCH_FLAT)
         c = {1, 0, 0, 2};
-    // 192-pixel x 64-channel flat tiles where none of the above applies: 64 or 192 output channels on maps no 2-D
-    // tile divides.  (Tried and dropped for wide outputs at a small minibatch, where the 128-channel tiles leave CUs
-    // idle: with 512 input channels one tile's serial reduction loop alone takes 55 us, longer than the generic
-    // kernel with a split reduction.)
+    // 192-pixel x 64-channel flat tiles where none of the above applies (64 or 192 output channels on maps no 2-D
+    // tile divides), and for wide outputs at a small minibatch where they beat the generic kernel
     if (c.fn == 0 && g.M >= 192 * 4 && max_flat_patch(g, 192) <= MAX_PATCH_FLAT64) c = {1, 0, 0, 3};
+    if (c.fn != 0 && c.variant >= 1 && c.variant <= 2 &&
+        (long)((g.M + 223) / 224) * (g.Ncols / 128) < kNumCU * 3 / 4 && flat64_wins_small_batch(g))
+        c = {1, 0, 0, 3};
     return c;
 }
 }  // namespace
@@ -521,7 +536,7 @@ bool tile2d_preferred(const GemmGeom& g) {
     if (c.variant == 0) return g.Ncols <= 128;
     if (c.variant == 3) {  // measured against the generic tap-by-tap kernel (64 channels) and conv_patch (wider)
         const long t3 = (long)((g.M + 191) / 192) * (g.Ncols / 64);
-        return g.Ncols == 64 ? t3 >= 48 : t3 >= 200;
+        return g.Ncols == 64 ? t3 >= 48 : (t3 >= 200 || flat64_wins_small_batch(g));
     }
     return (long)((g.M + 223) / 224) * (g.Ncols / 128) >= kNumCU * 3 / 4;
 }
