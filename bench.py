@@ -142,13 +142,18 @@ def cpu_baseline(net, image):
 
 
 def load_traffic(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, if any."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (the "scaled HBM MB / launch"
+    column of profiles/vgg16_b64_hbm_traffic.md), if the summary lists it."""
+    path = os.path.join(ROOT, "profiles", "vgg16_b64_hbm_traffic.md")
     try:
         with open(path) as f:
-            return json.load(f).get(kernel)
+            for line in f:
+                cells = [c.strip() for c in line.split("|")]
+                if len(cells) >= 8 and cells[1].strip("`").replace(" ", "") == kernel.replace(" ", ""):
+                    return float(cells[5]) * 1e6
     except (OSError, ValueError):
-        return None
+        pass
+    return None
 
 
 def main():
