@@ -76,3 +76,36 @@ def test_random_conv_shapes_match_oracle(orc, seed, ncase):
         if not ok:
             bad.append((shape, [f"{v:.2e}" for v in e]))
     assert not bad, bad
+
+
+def test_random_fc_shapes_match_oracle(orc):
+    """Seeded random FC shapes (batch 1..300, widths 8..5000, odd sizes included): forward with bias + ReLU, data
+    gradient and weight gradient against the oracle, whatever tile and split count the shape picks."""
+    import paper_1811_01532_amd as wap
+    rng = np.random.default_rng(31)
+    bad = []
+    for ci in range(40):
+        B = int(rng.choice([1, 2, 5, 8, 16, 31, 32, 64, 100, 128, 257, 300]))
+        n_in = int(rng.choice([8, 24, 100, 256, 1000, 1024, 2048, 4096, 4104, 5000]))
+        n_out = int(rng.choice([8, 10, 37, 64, 125, 512, 1000, 1024, 4096]))
+        print(f"[case] fc sweep #{ci} B={B} in={n_in} out={n_out}", flush=True)
+        xb = si.normal_bf16(si.rng(9500 + ci, 0), (B, n_in))
+        Wb = si.he_weight_bf16(si.rng(9500 + ci, 1), (n_out, n_in))
+        gb = si.normal_bf16(si.rng(9500 + ci, 2), (B, n_out))
+        bias = si.rng(9500 + ci, 3).standard_normal(n_out).astype(np.float32)
+        x64, W64, g64 = orc.bf16_bits_to_f64(xb), orc.bf16_bits_to_f64(Wb), orc.bf16_bits_to_f64(gb)
+        xd, Wd, gd = gu.dev_bf16(xb), gu.dev_bf16(Wb), gu.dev_bf16(gb)
+        d = wap.fc_desc(B, n_in, n_out, relu=True)
+        ws = gu.workspace(max(wap.wap_fc_workspace_bytes(d, p) for p in (0, 1, 2)))
+        y = torch.full((B, n_out), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dx = torch.full((B, n_in), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dW = torch.full((n_out, n_in), float("nan"), dtype=torch.float32, device="cuda")
+        wap.wap_fc_fwd(d, xd, Wd, torch.from_numpy(bias).cuda(), y, ws)
+        wap.wap_fc_bwd(d, xd, Wd, gd, dx, dW, ws)
+        torch.cuda.synchronize()
+        e = [gu.rel_err(gu.host_f64(y), orc.fc_fwd(x64, W64, bias=bias.astype(np.float64), relu=True)),
+             gu.rel_err(gu.host_f64(dx), orc.fc_bwd_data(g64, W64)),
+             gu.rel_err(gu.host_f64(dW), orc.fc_bwd_weight(g64, x64))]
+        if not (e[0] <= gu.TOL_BF16_OUT and e[1] <= gu.TOL_BF16_OUT and e[2] <= gu.TOL_F32_OUT):
+            bad.append(((B, n_in, n_out), [f"{v:.2e}" for v in e]))
+    assert not bad, bad
