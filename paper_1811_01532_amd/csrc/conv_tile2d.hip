@@ -29,6 +29,14 @@ constexpr int PITCH = (BK + 8) * 2;  // 144 bytes per padded pixel
 constexpr int MAX_PATCH = 352;       // padded pixels (>= (tile h + R - 1) * (tile w + S - 1)); also the staging area
 constexpr int MAX_PATCH_FLAT = 384;  // the same for flat (raster-order) tiles, which may straddle rows and images
 constexpr int MAX_PATCH_FLAT64 = 512;  // flat 192-pixel x 64-channel tiles (5x5 filters on 27-wide maps, across images)
+// LDS rows.  A 32-pixel fragment whose pixels wrap from one patch row to the next (flat tiles, 28-wide strips) reads
+// LDS rows with a gap at the wrap; the 16 lanes a ds_read_b128 serves per cycle then no longer hit 16 distinct
+// 16-byte bank groups (row r sits in group 9 r mod 16 at the 144-byte pitch) and the read takes ~7.4 instead of 4
+// cycles.  Giving every patch row 16 surplus LDS rows (row stride = width + 16) makes the gap a multiple of 16 rows
+// and the reads conflict-free again; the surplus rows are never read or written.  Two work-groups must still fit
+// the CU's 160 KB, else the dense layout is used.
+constexpr int LDS_ROWS_FLAT = 560;   // 2 x 560 x 144 B = 161280 B
+constexpr int LDS_ROWS_STRIP = 448;  // 8 x 28 strips: (8 + R - 1) x (28 + 16)
 
 struct TArgs {
     const bf16_t* A;
@@ -41,7 +49,9 @@ struct TArgs {
     uint8_t* pool_am;    // ... and the position r*2+s of the first maximum of every window
     GemmGeom g;
     int tiles_x, tiles_y, tiles_img, tiles_m, tiles_n;
-    int PWp, patch_len;  // padded tile (flat tiles: image) width, padded pixels per patch (2-D tiles)
+    int PWp, patch_len;  // LDS row stride of a patch row (>= RW), patch pixels to load (2-D tiles)
+    int RW;              // patch row width in pixels: tile (flat tiles: image) width + S - 1
+    FastDiv dRW, dRPHW;  // division by RW and (flat tiles) by PH * RW
     int PH;              // flat tiles: padded image height
     int relu;
     unsigned a_bytes, w_bytes;
@@ -97,7 +107,10 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
     constexpr int TWD = FLAT ? 1 : TW;  // divisor that is never zero
     constexpr int TH = BM / TWD;
     static_assert(FLAT || TH * TW == BM, "tile width must divide the tile");
+    // PATCH_ROWS: most patch pixels to load (sizes the per-thread vector list); LROWS: LDS rows behind them
+    constexpr bool SPREAD = FLAT || TW == 28;  // fragments wrap patch rows: the LDS row stride may exceed the row width
     constexpr int PATCH_ROWS = FLAT ? (PG == 2 ? MAX_PATCH_FLAT64 : MAX_PATCH_FLAT) : MAX_PATCH;
+    constexpr int LROWS = FLAT ? LDS_ROWS_FLAT : (TW == 28 ? LDS_ROWS_STRIP : MAX_PATCH);
     constexpr int PV = (PATCH_ROWS * 8 + NT - 1) / NT;  // 16-byte patch vectors per thread
     extern __shared__ __align__(16) unsigned char smem[];
     const GemmGeom& g = a.g;
@@ -124,7 +137,16 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
     const int m0 = tm * BM;
     const int m_last = (m0 + BM <= g.M ? m0 + BM : g.M) - 1;
     const int p_lo = FLAT ? pflat(m0) : 0;
-    const int patch_len = FLAT ? pflat(m_last) + (g.R - 1) * a.PWp + (g.S - 1) + 1 - p_lo : a.patch_len;
+    // the same in units of patch pixels (rows RW wide): what is loaded
+    const int RPHW = a.PH * a.RW;
+    auto rflat = [&](int m) {
+        int n = (int)fdiv((uint32_t)m, a.dOHW);
+        int rem = m - n * OHW;
+        int oh = (int)fdiv((uint32_t)rem, a.dOW);
+        return n * RPHW + oh * a.RW + (rem - oh * g.OW);
+    };
+    const int r_lo = FLAT ? rflat(m0) : 0;
+    const int patch_len = FLAT ? rflat(m_last) + (g.R - 1) * a.RW + (g.S - 1) + 1 - r_lo : a.patch_len;
     const int RS = g.R * g.S;
     const int ncs = g.IC / BK;
 
@@ -142,19 +164,23 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
     // the pixel's position (ih % 2) * 2 + iw % 2 inside the window, 2 bits per vector ----
     constexpr bool UNITS = UP && !FLAT;  // 2-D tiles: a thread fetches whole pooling windows instead (below)
     unsigned pvoff[UNITS ? 1 : PV];
+    int plrow[(SPREAD && !UNITS) ? PV : 1];  // LDS row of each vector's pixel (-1: none); dense layouts use the index itself
     unsigned pvcode = 0;
 #pragma unroll
     for (int i = 0; i < (UNITS ? 0 : PV); ++i) {
         int v = tid + i * NT;
         int q = v >> 3;
         unsigned off = OOB;
+        if (SPREAD) plrow[i] = -1;
         if (q < patch_len) {
             if (FLAT) {
-                int p = p_lo + q;
-                int n = (int)fdiv((uint32_t)p, a.dPHW);
-                int rem = p - n * PHW;
-                int vh = (int)fdiv((uint32_t)rem, a.dPWp);
-                int ih = vh - g.pad_h, iw = rem - vh * a.PWp - g.pad_w;
+                int p = r_lo + q;
+                int n = (int)fdiv((uint32_t)p, a.dRPHW);
+                int rem = p - n * RPHW;
+                int vh = (int)fdiv((uint32_t)rem, a.dRW);
+                int pxp = rem - vh * a.RW;
+                int ih = vh - g.pad_h, iw = pxp - g.pad_w;
+                plrow[i] = n * PHW + vh * a.PWp + pxp - p_lo;
                 if (n * OHW < g.M && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW) {
                     if (UP) {
                         off = (unsigned)(((n * IH2 + (ih >> 1)) * IW2 + (iw >> 1)) * g.IC + (v & 7) * 8) * 2u;
@@ -164,9 +190,10 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
                     }
                 }
             } else {
-                int py = (int)fdiv((uint32_t)q, a.dPWp);
-                int px = q - py * a.PWp;
+                int py = (int)fdiv((uint32_t)q, a.dRW);
+                int px = q - py * a.RW;
                 int ih = oh0 - g.pad_h + py, iw = ow0 - g.pad_w + px;
+                if (SPREAD) plrow[i] = py * a.PWp + px;
                 if ((unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW) {
                     if (UP) {
                         off = (unsigned)(((img * IH2 + (ih >> 1)) * IW2 + (iw >> 1)) * g.IC + (v & 7) * 8) * 2u;
@@ -204,7 +231,7 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
             uoff[i] = off;
             uq0[i] = py * a.PWp + px;
             if (unit < a.units) {
-                const unsigned vy0 = py >= 0, vy1 = py + 1 < PHt, vx0 = px >= 0, vx1 = px + 1 < a.PWp;
+                const unsigned vy0 = py >= 0, vy1 = py + 1 < PHt, vx0 = px >= 0, vx1 = px + 1 < a.RW;
                 uval |= ((vy0 & vx0) | ((vy0 & vx1) << 1) | ((vy1 & vx0) << 2) | ((vy1 & vx1) << 3)) << (4 * i);
             }
         }
@@ -286,7 +313,11 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
 #pragma unroll
             for (int i = 0; i < PV; ++i) {
                 int v = tid + i * NT;
-                if ((v >> 3) < PATCH_ROWS) *reinterpret_cast<u32x4*>(smem + (v >> 3) * PITCH + (v & 7) * 16) = rp[i];
+                if (SPREAD) {
+                    if (plrow[i] >= 0) *reinterpret_cast<u32x4*>(smem + plrow[i] * PITCH + (v & 7) * 16) = rp[i];
+                } else if ((v >> 3) < PATCH_ROWS) {
+                    *reinterpret_cast<u32x4*>(smem + (v >> 3) * PITCH + (v & 7) * 16) = rp[i];
+                }
             }
         }
         __syncthreads();
@@ -347,7 +378,7 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
     constexpr int VPR = BN / 8;          // 16-byte vectors per pixel row
     constexpr int RPP = NT / VPR;        // pixel rows stored per pass
     // fragments of every pixel group staged per pass: as many as fit the (dead) patch area
-    constexpr int JFIT = (PATCH_ROWS * PITCH) / (OPITCH * 32 * PG);
+    constexpr int JFIT = (LROWS * PITCH) / (OPITCH * 32 * PG);
     constexpr int JN = JFIT < FM ? JFIT : FM;
     constexpr int HROWS = PG * JN * 32;
     static_assert(JN >= 1, "staging area too small");
@@ -437,7 +468,7 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
 template <int FN, int TW, int FM, int PG, bool UP>
 int launch_tile2d_u(const TArgs& ta, hipStream_t st) {
     auto kfn = conv_tile2d_kernel<FN, TW, FM, PG, UP>;
-    constexpr size_t smem = (size_t)(TW == 0 ? (PG == 2 ? MAX_PATCH_FLAT64 : MAX_PATCH_FLAT) : MAX_PATCH) * PITCH;
+    constexpr size_t smem = (size_t)(TW == 0 ? LDS_ROWS_FLAT : (TW == 28 ? LDS_ROWS_STRIP : MAX_PATCH)) * PITCH;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
@@ -461,9 +492,9 @@ struct TileCfg {
                               // 128 channels; 2: the same with flat tiles (224 consecutive pixels); 3: flat tiles of
                               // 192 pixels x 64 channels (2 x 3 fragments) for thin outputs on maps no 2-D tile divides
 };
-// largest flat patch (in padded pixels) any bm-pixel raster-order tile of this geometry needs
-int max_flat_patch(const GemmGeom& g, int bm) {
-    const int PH = g.OH + g.R - 1, PW = g.OW + g.S - 1;
+// largest flat patch (in rows of the given stride; 0: the dense width) any bm-pixel raster-order tile of this geometry needs
+int max_flat_patch(const GemmGeom& g, int bm, int stride = 0) {
+    const int PH = g.OH + g.R - 1, PW = stride > 0 ? stride : g.OW + g.S - 1;
     const long OHW = (long)g.OH * g.OW;
     auto pflat = [&](long m) {
         long n = m / OHW, rem = m - n * OHW;
@@ -598,7 +629,10 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
         ta.tiles_x = ta.tiles_y = ta.tiles_img = 1;
         ta.tiles_m = (g.M + bm - 1) / bm;
         ta.PH = g.OH + g.R - 1;
-        ta.PWp = g.OW + g.S - 1;
+        ta.RW = g.OW + g.S - 1;
+        ta.PWp = ta.RW;
+        if (g.S - 1 <= 16 && max_flat_patch(g, bm, g.OW + 16) <= LDS_ROWS_FLAT) ta.PWp = g.OW + 16;  // conflict-free stride
+        ta.dRPHW = make_fastdiv((uint32_t)(ta.PH * ta.RW));
         ta.patch_len = 0;  // per tile, computed in the kernel
         ta.dOHW = make_fastdiv((uint32_t)(g.OH * g.OW));
         ta.dOW = make_fastdiv((uint32_t)g.OW);
@@ -608,8 +642,10 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
         ta.tiles_y = g.OH / c.th;
         ta.tiles_img = ta.tiles_x * ta.tiles_y;
         ta.tiles_m = ta.tiles_img * (g.M / (g.OH * g.OW));
-        ta.PWp = c.tw + g.S - 1;
-        ta.patch_len = (c.th + g.R - 1) * ta.PWp;
+        ta.RW = c.tw + g.S - 1;
+        ta.PWp = ta.RW;
+        if (c.variant == 1 && g.S - 1 <= 16 && (c.th + g.R - 1) * (c.tw + 16) <= LDS_ROWS_STRIP) ta.PWp = c.tw + 16;
+        ta.patch_len = (c.th + g.R - 1) * ta.RW;
         // windows that can touch the patch: its first pixel may be the second of its window
         ta.UW = (c.tw + g.S - 1) / 2 + 1;
         ta.units = ((c.th + g.R - 1) / 2 + 1) * ta.UW;
@@ -621,6 +657,7 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
     ta.dTimg = make_fastdiv((uint32_t)ta.tiles_img);
     ta.dTx = make_fastdiv((uint32_t)ta.tiles_x);
     ta.dPWp = make_fastdiv((uint32_t)ta.PWp);
+    ta.dRW = make_fastdiv((uint32_t)ta.RW);
     if (c.variant == 1) return launch_tile2d_t<1, 28, 7, 1>(ta, st);
     if (c.variant == 2) return launch_tile2d_t<1, 0, 7, 1>(ta, st);
     if (c.variant == 3) return launch_tile2d_t<1, 0, 3, 2>(ta, st);
