@@ -328,6 +328,7 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
         bf16x8 fa[2][FM];
 #pragma unroll
         for (int j = 0; j < FM; ++j) fa[0][j] = *reinterpret_cast<const bf16x8*>(smem + frow[j]);
+        __builtin_amdgcn_s_setprio(1);
         int r = 0, s = 0;
         for (int tap = 0; tap < RS; ++tap) {
             const bool last = tap + 1 == RS;
@@ -370,6 +371,7 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
             r = r1;
             s = s1;
         }
+        __builtin_amdgcn_s_setprio(0);
     }
 
     // ---- epilogue: bias / ReLU / bf16, transposed through LDS (the patch is dead) so that every global store
