@@ -512,16 +512,17 @@ int max_flat_patch(const GemmGeom& g, int bm, int stride = 0) {
     return (int)worst;
 }
 // Wide outputs at a small minibatch: the 128-channel tiles leave most CUs without work and conv_patch.hip does not
-// apply, so the alternative is the generic tap-by-tap kernel with a split reduction (measured ~380 TFLOP/s there).
-// One 192 x 64 tile's serial reduction loop takes ~6.6 us per 64-channel slice of a 3x3 filter whatever the
-// minibatch, so the flat tiles win only once the layer holds enough work.
+// apply, so the alternative is the generic tap-by-tap kernel with a split reduction (measured 270-390 TFLOP/s there,
+// plus ~9 us for the launch of its reduction epilogue).  One 192 x 64 tile's serial reduction loop takes 5.4-6.6 us
+// per 64-channel slice of a 3x3 filter whatever the minibatch, so the flat tiles win only once the layer holds
+// enough work.
 bool flat64_wins_small_batch(const GemmGeom& g) {
     if ((g.Ncols % 64) != 0 || g.Ncols <= 64 || g.M >= 224 * 32 || g.M < 192 * 4) return false;
     if ((long)((g.M + 191) / 192) * (g.Ncols / 64) < 64) return false;
     if (max_flat_patch(g, 192) > MAX_PATCH_FLAT64) return false;
     const double flops = 2.0 * g.M * (double)g.Ncols * g.Kred;
-    const double t_generic = flops / 380e12;
-    const double floor_s = 6.6e-6 * (g.IC / 64) * (g.R * g.S / 9.0);
+    const double t_generic = flops / 330e12 + 9e-6;
+    const double floor_s = 5.5e-6 * (g.IC / 64) * (g.R * g.S / 9.0);
     const double t_flat = floor_s > flops / 900e12 ? floor_s : flops / 900e12;
     return t_flat < 0.85 * t_generic;
 }
