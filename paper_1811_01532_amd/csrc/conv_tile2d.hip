@@ -384,6 +384,7 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
     constexpr int JN = JFIT < FM ? JFIT : FM;
     constexpr int HROWS = PG * JN * 32;
     static_assert(JN >= 1, "staging area too small");
+    static_assert(TW != 28 || JN == FM, "the strip tile must be staged in one pass (the fused pool relies on it)");
 #pragma unroll
     for (int half = 0; half < (FM + JN - 1) / JN; ++half) {
         __syncthreads();  // previous readers of the staging area (or of the patch) are done
@@ -429,7 +430,8 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
         // ---- fused 2x2 / stride-2 max-pool of the staged (bias / ReLU applied, bf16) tile: tile origin and size
         // are even, and both rows of a window are staged in the same pass (a 32-pixel fragment holds whole tile
         // rows and passes hold fragment pairs).  Same rule as maxpool_fwd_kernel: first maximum in (r, s) order. ----
-        if (!FLAT && PG == 2 && FM == 4 && a.pool_y) {
+        // The 8 x 28 strips stage their whole tile in one pass (JN == FM), so every window is complete there as well.
+        if (!FLAT && ((PG == 2 && FM == 4) || (TW == 28 && JN == FM)) && a.pool_y) {
             constexpr int PWT = TWD / 2;  // pooled pixels per tile row
             auto srow_of = [&](int idx) {
                 const int f = idx >> 5;
@@ -603,7 +605,8 @@ bool tile2d_fuses_unpool(const GemmGeom& g) {
 // can the epilogue also emit the 2x2 / stride-2 max-pool of the output?
 bool tile2d_fuses_pool(const GemmGeom& g) {
     if (!tile2d_supported(g)) return false;
-    return tile_cfg(g).variant == 0;  // even tile origin and size, whole windows per staging pass
+    const TileCfg c = tile_cfg(g);  // even tile origin and size, whole windows per staging pass
+    return c.variant == 0 || c.variant == 1;  // strips stage the whole 224 x 128 tile in one pass
 }
 
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
