@@ -52,6 +52,7 @@ struct TArgs {
     int PWp, patch_len;  // LDS row stride of a patch row (>= RW), patch pixels to load (2-D tiles)
     int RW;              // patch row width in pixels: tile (flat tiles: image) width + S - 1
     FastDiv dRW, dRPHW;  // division by RW and (flat tiles) by PH * RW
+    FastDiv dOW2;        // flat tiles with the fused pool: division by OW / 2
     int PH;              // flat tiles: padded image height
     int relu;
     unsigned a_bytes, w_bytes;
@@ -385,6 +386,7 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
     constexpr int HROWS = PG * JN * 32;
     static_assert(JN >= 1, "staging area too small");
     static_assert(TW != 28 || JN == FM, "the strip tile must be staged in one pass (the fused pool relies on it)");
+    static_assert(!(FLAT && PG == 1 && FM == 7) || JN == FM, "the flat 224-pixel tile must be staged in one pass");
 #pragma unroll
     for (int half = 0; half < (FM + JN - 1) / JN; ++half) {
         __syncthreads();  // previous readers of the staging area (or of the patch) are done
@@ -430,19 +432,25 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
         // ---- fused 2x2 / stride-2 max-pool of the staged (bias / ReLU applied, bf16) tile: tile origin and size
         // are even, and both rows of a window are staged in the same pass (a 32-pixel fragment holds whole tile
         // rows and passes hold fragment pairs).  Same rule as maxpool_fwd_kernel: first maximum in (r, s) order. ----
-        // The 8 x 28 strips stage their whole tile in one pass (JN == FM), so every window is complete there as well.
-        if (!FLAT && ((PG == 2 && FM == 4) || (TW == 28 && JN == FM)) && a.pool_y) {
-            constexpr int PWT = TWD / 2;  // pooled pixels per tile row
+        // The 8 x 28 strips and the flat 224-pixel tiles stage their whole tile in one pass (JN == FM), so every window
+        // is complete there as well; a flat tile is then a whole number of row pairs (the host checks 224 % (2 OW) == 0
+        // and even map sizes), possibly of two images.
+        constexpr bool POOLS = FLAT ? (PG == 1 && JN == FM) : ((PG == 2 && FM == 4) || (TW == 28 && JN == FM));
+        if (POOLS && a.pool_y) {
+            const int roww = FLAT ? g.OW : TWD;  // pixels per tile row
+            const int PWT = roww >> 1;           // pooled pixels per tile row
             auto srow_of = [&](int idx) {
                 const int f = idx >> 5;
                 return ((f / FM) * JN + (f % FM) - half * JN) * 32 + (idx & 31);
             };
             for (int item = tid; item < (BM / 4) * VPR; item += NT) {
                 const int pp = item / VPR, vec = item % VPR;
-                const int py = pp / PWT, px = pp % PWT;
-                const int idx00 = (2 * py) * TWD + 2 * px;
+                const int py = FLAT ? (int)fdiv((uint32_t)pp, a.dOW2) : pp / (TWD / 2);
+                const int px = pp - py * PWT;
+                const int idx00 = (2 * py) * roww + 2 * px;
                 if ((((idx00 >> 5) % FM) / JN) != half) continue;  // window staged in the other pass
-                const int idx4[4] = {idx00, idx00 + 1, idx00 + TWD, idx00 + TWD + 1};
+                if (FLAT && m0 + idx00 + roww + 1 > m_last) continue;  // beyond the last pixel of the layer
+                const int idx4[4] = {idx00, idx00 + 1, idx00 + roww, idx00 + roww + 1};
                 unsigned short best[8];
                 float bestf[8];
                 unsigned char bi[8];
@@ -456,7 +464,16 @@ __global__ __launch_bounds__(NT, (FN * FM <= 4 && TW != 0 ? 3 : 2)) void conv_ti
                         if (k == 0 || f > bestf[e]) { bestf[e] = f; best[e] = bits; bi[e] = (unsigned char)k; }
                     }
                 }
-                const size_t po = ((size_t)(img * (g.OH / 2) + oh0 / 2 + py) * (g.OW / 2) + ow0 / 2 + px) * g.Ncols + n0 + vec * 8;
+                size_t po;
+                if (FLAT) {
+                    const int m = m0 + idx00;
+                    const int n = (int)fdiv((uint32_t)m, a.dOHW);
+                    const int rem = m - n * OHW;
+                    const int oh = (int)fdiv((uint32_t)rem, a.dOW), ow = rem - oh * g.OW;
+                    po = ((size_t)(n * (g.OH / 2) + oh / 2) * (g.OW / 2) + ow / 2) * g.Ncols + n0 + vec * 8;
+                } else {
+                    po = ((size_t)(img * (g.OH / 2) + oh0 / 2 + py) * (g.OW / 2) + ow0 / 2 + px) * g.Ncols + n0 + vec * 8;
+                }
                 u32x4 yo = {(unsigned)best[0] | ((unsigned)best[1] << 16), (unsigned)best[2] | ((unsigned)best[3] << 16),
                             (unsigned)best[4] | ((unsigned)best[5] << 16), (unsigned)best[6] | ((unsigned)best[7] << 16)};
                 *reinterpret_cast<u32x4*>(a.pool_y + po) = yo;
@@ -606,7 +623,9 @@ bool tile2d_fuses_unpool(const GemmGeom& g) {
 bool tile2d_fuses_pool(const GemmGeom& g) {
     if (!tile2d_supported(g)) return false;
     const TileCfg c = tile_cfg(g);  // even tile origin and size, whole windows per staging pass
-    return c.variant == 0 || c.variant == 1;  // strips stage the whole 224 x 128 tile in one pass
+    if (c.variant == 0 || c.variant == 1) return true;  // strips stage the whole 224 x 128 tile in one pass
+    // flat 224 x 128 tiles: whole row pairs per tile
+    return c.variant == 2 && (g.OH % 2) == 0 && (g.OW % 2) == 0 && (224 % (2 * g.OW)) == 0;
 }
 
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
@@ -642,6 +661,7 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
         ta.patch_len = 0;  // per tile, computed in the kernel
         ta.dOHW = make_fastdiv((uint32_t)(g.OH * g.OW));
         ta.dOW = make_fastdiv((uint32_t)g.OW);
+        ta.dOW2 = make_fastdiv((uint32_t)(g.OW / 2 > 0 ? g.OW / 2 : 1));
         ta.dPHW = make_fastdiv((uint32_t)(ta.PH * ta.PWp));
     } else {
         ta.tiles_x = g.OW / c.tw;
