@@ -186,6 +186,21 @@ int wap_softmax_xent_grad(int32_t B, int32_t classes, const void* z, const int32
  * n elements; w_bf16 may be NULL. */
 int wap_sgd_update(int64_t n, float* w32, const float* dw, float lr, void* w_bf16, void* stream);
 
+/* Weight gradient and SGD update of one layer in one call (the weight-update tail of the backward time t_b,
+ * Eq. 1): w32 <- w32 - lr * dw, w_bf16 <- bf16(w32), with dw exactly what wap_conv2d_bwd_weight / wap_fc_bwd
+ * compute, and the same fused multiply-add and rounding as wap_sgd_update: bit for bit the result of those
+ * two calls.  w32: fp32 master weights, w_bf16: bf16 compute copy (both required, 16-byte aligned, layout of
+ * the layer's weights).  Where the kernel that finishes the gradient applies the update itself (the matching
+ * *_sgd_fused query reports 1) the gradient is never stored and dw_scratch may be NULL; otherwise dw_scratch
+ * (fp32, one element per weight, device) is required and the two kernels run back to back.  The caller must
+ * have finished every product that reads this step's weights (the layer's data gradient) first. */
+int wap_conv2d_bwd_weight_sgd(const wap_conv_desc* d, const void* x, const void* dy, float* w32, void* w_bf16,
+                              float lr, float* dw_scratch, void* ws, size_t ws_bytes, void* stream);
+int wap_fc_bwd_weight_sgd(const wap_fc_desc* d, const void* x, const void* dy, float* w32, void* w_bf16,
+                          float lr, float* dw_scratch, void* ws, size_t ws_bytes, void* stream);
+int wap_conv2d_bwd_weight_sgd_fused(const wap_conv_desc* d, int32_t* fused_out);
+int wap_fc_bwd_weight_sgd_fused(const wap_fc_desc* d, int32_t* fused_out);
+
 /* fp32 -> bf16 copy of n elements (used to derive the compute copy of freshly set master weights). */
 int wap_cast_f32_bf16(int64_t n, const float* src, void* dst, void* stream);
 

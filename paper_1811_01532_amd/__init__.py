@@ -183,6 +183,30 @@ def wap_fc_bwd(desc, x, Wt, dy, dx, dW, ws=None, stream=None):
                             ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
 
 
+def wap_conv2d_bwd_weight_sgd(desc, x, dy, w32, w_bf16, lr, dw_scratch=None, ws=None, stream=None):
+    _check(lib().wap_conv2d_bwd_weight_sgd(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(w32), _ptr(w_bf16),
+                                           ctypes.c_float(lr), _ptr(dw_scratch), _ptr(ws),
+                                           ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
+
+
+def wap_fc_bwd_weight_sgd(desc, x, dy, w32, w_bf16, lr, dw_scratch=None, ws=None, stream=None):
+    _check(lib().wap_fc_bwd_weight_sgd(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(w32), _ptr(w_bf16),
+                                       ctypes.c_float(lr), _ptr(dw_scratch), _ptr(ws),
+                                       ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
+
+
+def wap_conv2d_bwd_weight_sgd_fused(desc):
+    out = ctypes.c_int32(0)
+    _check(lib().wap_conv2d_bwd_weight_sgd_fused(ctypes.byref(desc), ctypes.byref(out)))
+    return bool(out.value)
+
+
+def wap_fc_bwd_weight_sgd_fused(desc):
+    out = ctypes.c_int32(0)
+    _check(lib().wap_fc_bwd_weight_sgd_fused(ctypes.byref(desc), ctypes.byref(out)))
+    return bool(out.value)
+
+
 def wap_relu_bwd(dy, y, dx, n, stream=None):
     _check(lib().wap_relu_bwd(_ptr(dy), _ptr(y), _ptr(dx), ctypes.c_int64(n), _stream(stream)))
 

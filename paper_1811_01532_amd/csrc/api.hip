@@ -248,6 +248,53 @@ int wap_conv2d_bwd_weight(const wap_conv_desc* d, const void* x, const void* dy,
     return launch_wgrad(g, p, (const bf16_t*)x, (const bf16_t*)dy, dw, ws, (hipStream_t)stream);
 }
 
+static int bwd_weight_sgd(const WgradGeom& g, const void* x, const void* dy, float* w32, void* w_bf16, float lr,
+                          float* dw_scratch, void* ws, size_t ws_bytes, void* stream) {
+    WAP_TRY(check_ptr(x, "x"));
+    WAP_TRY(check_ptr(dy, "dy"));
+    WAP_TRY(check_ptr(w32, "w32"));
+    WAP_TRY(check_ptr(w_bf16, "w_bf16"));
+    WgradPlan p = plan_wgrad(g);
+    WAP_TRY(check_ws(p.ws_bytes, ws, ws_bytes));
+    hipStream_t st = (hipStream_t)stream;
+    if (wgrad_fuses_sgd(g, p)) {
+        const SgdFuse sgd = {w32, (bf16_t*)w_bf16, lr};
+        return launch_wgrad(g, p, (const bf16_t*)x, (const bf16_t*)dy, nullptr, ws, st, nullptr, nullptr, &sgd);
+    }
+    if (!dw_scratch) return set_error(WAP_EINVAL, "bwd_weight_sgd: dw_scratch is NULL and this shape does not fuse the update");
+    if (!aligned16(dw_scratch)) return set_error(WAP_EINVAL, "dw_scratch is not 16-byte aligned");
+    WAP_TRY(launch_wgrad(g, p, (const bf16_t*)x, (const bf16_t*)dy, dw_scratch, ws, st));
+    return launch_sgd((size_t)g.K * g.R * g.S * g.C, w32, dw_scratch, lr, (bf16_t*)w_bf16, st);
+}
+
+int wap_conv2d_bwd_weight_sgd(const wap_conv_desc* d, const void* x, const void* dy, float* w32, void* w_bf16,
+                              float lr, float* dw_scratch, void* ws, size_t ws_bytes, void* stream) {
+    WAP_TRY(validate_conv(d));
+    return bwd_weight_sgd(geom_conv_wgrad(*d), x, dy, w32, w_bf16, lr, dw_scratch, ws, ws_bytes, stream);
+}
+
+int wap_fc_bwd_weight_sgd(const wap_fc_desc* d, const void* x, const void* dy, float* w32, void* w_bf16,
+                          float lr, float* dw_scratch, void* ws, size_t ws_bytes, void* stream) {
+    WAP_TRY(validate_fc(d));
+    return bwd_weight_sgd(geom_fc_dw(*d), x, dy, w32, w_bf16, lr, dw_scratch, ws, ws_bytes, stream);
+}
+
+int wap_conv2d_bwd_weight_sgd_fused(const wap_conv_desc* d, int32_t* fused_out) {
+    WAP_TRY(validate_conv(d));
+    if (!fused_out) return set_error(WAP_EINVAL, "fused_out is NULL");
+    WgradGeom g = geom_conv_wgrad(*d);
+    *fused_out = wgrad_fuses_sgd(g, plan_wgrad(g)) ? 1 : 0;
+    return WAP_OK;
+}
+
+int wap_fc_bwd_weight_sgd_fused(const wap_fc_desc* d, int32_t* fused_out) {
+    WAP_TRY(validate_fc(d));
+    if (!fused_out) return set_error(WAP_EINVAL, "fused_out is NULL");
+    WgradGeom g = geom_fc_dw(*d);
+    *fused_out = wgrad_fuses_sgd(g, plan_wgrad(g)) ? 1 : 0;
+    return WAP_OK;
+}
+
 static int check_pool2x2_bwd(const wap_conv_desc* d, const void* g_pool, const uint8_t* argmax) {
     WAP_TRY(validate_conv(d));
     WAP_TRY(check_ptr(g_pool, "g_pool"));

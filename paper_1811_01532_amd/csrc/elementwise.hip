@@ -60,8 +60,9 @@ __global__ void reduce_bf16_kernel(const float* __restrict__ part, int nsplit, s
     }
 }
 
+// With a parameter block (sgd.w32 != NULL) the sums update the parameters instead of being stored.
 __global__ void reduce_f32_kernel(const float* __restrict__ part, int nsplit, size_t elems,
-                                  float* __restrict__ out) {
+                                  float* __restrict__ out, const SgdFuse sgd) {
     size_t stride = (size_t)gridDim.x * blockDim.x;
     if ((elems & 3) == 0) {
         size_t n4 = elems / 4;
@@ -71,13 +72,20 @@ __global__ void reduce_f32_kernel(const float* __restrict__ part, int nsplit, si
                 float4 t = reinterpret_cast<const float4*>(part + (size_t)k * elems)[i];
                 s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
             }
-            reinterpret_cast<float4*>(out)[i] = s;
+            if (sgd.w32) sgd_apply4(sgd.w32 + i * 4, sgd.wb + i * 4, sgd.lr, s.x, s.y, s.z, s.w);
+            else reinterpret_cast<float4*>(out)[i] = s;
         }
     } else {
         for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < elems; i += stride) {
             float s = part[i];
             for (int k = 1; k < nsplit; ++k) s += part[(size_t)k * elems + i];
-            out[i] = s;
+            if (sgd.w32) {
+                float a = sgd_apply(sgd.w32[i], s, sgd.lr);
+                sgd.w32[i] = a;
+                sgd.wb[i] = f2bf(a);
+            } else {
+                out[i] = s;
+            }
         }
     }
 }
@@ -87,7 +95,7 @@ __global__ void reduce_f32_kernel(const float* __restrict__ part, int nsplit, si
 // group order through LDS.  The summation tree is fixed by (nsplit, G), so results are bitwise reproducible.
 template <int G>
 __global__ __launch_bounds__(256) void reduce_f32_grouped_kernel(const float* __restrict__ part, int nsplit, size_t elems,
-                                                               float* __restrict__ out) {
+                                                               float* __restrict__ out, const SgdFuse sgd) {
     constexpr int COLS = 256 / G;
     __shared__ float4 sm[G][COLS];
     const int col = threadIdx.x % COLS, grp = threadIdx.x / COLS;
@@ -118,7 +126,8 @@ __global__ __launch_bounds__(256) void reduce_f32_grouped_kernel(const float* __
             float4 t = sm[g2][col];
             s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
         }
-        reinterpret_cast<float4*>(out)[i] = s;
+        if (sgd.w32) sgd_apply4(sgd.w32 + i * 4, sgd.wb + i * 4, sgd.lr, s.x, s.y, s.z, s.w);
+        else reinterpret_cast<float4*>(out)[i] = s;
     }
 }
 
@@ -367,7 +376,8 @@ __global__ void sgd_kernel(size_t n, float* __restrict__ w, const float* __restr
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
         float4 a = reinterpret_cast<float4*>(w)[i];
         float4 g = reinterpret_cast<const float4*>(dw)[i];
-        a.x -= lr * g.x; a.y -= lr * g.y; a.z -= lr * g.z; a.w -= lr * g.w;
+        a.x = sgd_apply(a.x, g.x, lr); a.y = sgd_apply(a.y, g.y, lr);
+        a.z = sgd_apply(a.z, g.z, lr); a.w = sgd_apply(a.w, g.w, lr);
         reinterpret_cast<float4*>(w)[i] = a;
         if (wb) {
             uint2 pk;
@@ -377,7 +387,7 @@ __global__ void sgd_kernel(size_t n, float* __restrict__ w, const float* __restr
         }
     }
     for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-        float a = w[i] - lr * dw[i];
+        float a = sgd_apply(w[i], dw[i], lr);
         w[i] = a;
         if (wb) wb[i] = f2bf(a);
     }
@@ -417,20 +427,22 @@ int launch_reduce_bf16(const float* part, int nsplit, size_t elems, int ncols, c
     return check_launch("reduce_bf16");
 }
 
-int launch_reduce_f32(const float* part, int nsplit, size_t elems, float* out, hipStream_t st) {
+int launch_reduce_f32(const float* part, int nsplit, size_t elems, float* out, hipStream_t st, const SgdFuse* sgdp) {
+    SgdFuse sgd = {nullptr, nullptr, 0.f};
+    if (sgdp) sgd = *sgdp;
     if ((elems & 3) == 0 && nsplit >= 8) {
         const size_t n4 = elems / 4;
         if (nsplit >= 64) {
             hipLaunchKernelGGL(reduce_f32_grouped_kernel<32>, dim3((unsigned)((n4 + 7) / 8)), dim3(256), 0, st, part, nsplit,
-                               elems, out);
+                               elems, out, sgd);
         } else {
             hipLaunchKernelGGL(reduce_f32_grouped_kernel<8>, dim3((unsigned)((n4 + 31) / 32)), dim3(256), 0, st, part, nsplit,
-                               elems, out);
+                               elems, out, sgd);
         }
         return check_launch("reduce_f32_grouped");
     }
     hipLaunchKernelGGL(reduce_f32_kernel, dim3(grid_for(elems / 4 + 1)), dim3(kThreads), 0, st, part,
-                       nsplit, elems, out);
+                       nsplit, elems, out, sgd);
     return check_launch("reduce_f32");
 }
 

@@ -3,8 +3,10 @@
 // aggregations; its duration is the sum over layers of t_c in Eq. 1).  The plan owns no device
 // memory: every tensor lives at a fixed offset of one caller-provided arena, all launches go to
 // one stream, nothing allocates or synchronises in wap_step_run.
+#include <algorithm>
 #include <cstring>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "wap_internal.h"
@@ -39,6 +41,9 @@ struct Op {
     size_t tb = 0;
     bool unpool = false;    // conv backward whose dy operand is the gradient of the 2x2-pooled output, routed through the
                             // argmax by the kernel's loader (argmax at t5 for the data gradient, t3 for the weight gradient)
+    bool fuse_sgd = false;  // weight gradient that applies the SGD update itself (fp32 master weights at t6, bf16 copy at
+                            // t7); it runs after the layer's data gradient, which still needs the old weights
+    size_t t6 = 0, t7 = 0;
     int N = 0, H = 0, W = 0, C = 0, win = 0, st = 0;  // pooling / softmax shapes
     size_t n = 0;
     const char* kernel = "";  // kernel instantiation the operation launches
@@ -122,10 +127,12 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
                                    op.has_pool ? (uint8_t*)(base + op.t5) : nullptr,
                                    op.unpool ? (const uint8_t*)(base + op.t5) : nullptr);
         case OP_CONV_WGRAD:
-        case OP_FC_DW:
+        case OP_FC_DW: {
+            const SgdFuse sgd = {(float*)(base + op.t6), (bf16_t*)(base + op.t7), p->lr};
             return launch_wgrad(op.wg, op.wp, (const bf16_t*)(base + op.t0), (const bf16_t*)(base + op.t1),
                                 (float*)(base + op.t2), ws, st, ev_mid,
-                                op.unpool ? (const uint8_t*)(base + op.t3) : nullptr);
+                                op.unpool ? (const uint8_t*)(base + op.t3) : nullptr, op.fuse_sgd ? &sgd : nullptr);
+        }
         case OP_POOL_FWD:
             return launch_maxpool_fwd(op.N, op.H, op.W, op.C, op.win, op.st, (const bf16_t*)(base + op.t0),
                                       (bf16_t*)(base + op.t1), (uint8_t*)(base + op.t2), st);
@@ -307,14 +314,26 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         f.has_bias = true;
         f.tb = p->w32_off + boff[li] * 4;
     };
-    auto push_wgrad = [&](OpKind kind, const std::string& name, const WgradGeom& g, size_t x, size_t dy, size_t dw) {
+    // Parameter ranges [first, last) whose update is applied by the kernel that finishes the layer's weight gradient:
+    // the gradient is then neither stored nor read back.  The kept-gradients layout stores every gradient instead.
+    std::vector<std::pair<size_t, size_t>> fused_ranges;
+    auto push_wgrad = [&](OpKind kind, const std::string& name, const WgradGeom& g, size_t x, size_t dy, int li) {
         Op op;
         op.kind = kind; op.name = name; op.wg = g;
         op.wp = plan_wgrad(g);
         op.kernel = wgrad_kernel_name(g, op.wp);
-        op.flops = 2.0 * g.N * g.P * g.Q * (double)g.K * g.R * g.S * g.C;
-        op.bytes = 2.0 * ((double)g.N * g.H * g.W * g.C + (double)g.N * g.P * g.Q * g.K) + 4.0 * g.K * g.R * g.S * g.C;
-        op.t0 = x; op.t1 = dy; op.t2 = dw;
+        const double nw = (double)g.K * g.R * g.S * g.C;
+        op.flops = 2.0 * g.N * g.P * g.Q * nw;
+        op.bytes = 2.0 * ((double)g.N * g.H * g.W * g.C + (double)g.N * g.P * g.Q * g.K) + 4.0 * nw;
+        op.t0 = x; op.t1 = dy; op.t2 = p->dw_off + poff[li] * 4;
+        if (!keep && (poff[li] & 3) == 0 && wgrad_fuses_sgd(g, op.wp)) {
+            op.fuse_sgd = true;
+            op.t6 = p->w32_off + poff[li] * 4;
+            op.t7 = p->wb_off + poff[li] * 2;
+            op.name += "+sgd";
+            op.bytes += 6.0 * nw;  // master weights read and written, bf16 copy written, gradient not stored
+            fused_ranges.push_back({poff[li], poff[li] + (size_t)nw});
+        }
         if (op.wp.ws_bytes > ws_need) ws_need = op.wp.ws_bytes;
         p->ops.push_back(op);
     };
@@ -391,7 +410,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             p->ops.push_back(op);
             g_cur = op.t2;
         }
-        push_wgrad(OP_FC_DW, nm + ".dW", geom_fc_dw(fds[i]), fc_in[i], g_cur, p->dw_off + poff[nconv + i] * 4);
+        push_wgrad(OP_FC_DW, nm + ".dW", geom_fc_dw(fds[i]), fc_in[i], g_cur, nconv + i);
         push_bias_grad(nconv + i, (size_t)B, g_cur);
         if (!keep) gsel = (g_cur == gbuf[0]) ? 1 : 0;
         std::string in_name = i > 0 ? "g." + lname(nconv + i - 1) + ".y"
@@ -447,12 +466,12 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             g_cur = op.t2;
         }
         size_t x_in = i == 0 ? t_input : (convs[i - 1].pool_win ? pool_y[i - 1] : conv_y[i - 1]);
-        push_wgrad(OP_CONV_WGRAD, nm + ".wgrad", geom_conv_wgrad(d), x_in, g_cur, p->dw_off + poff[i] * 4);
+        push_wgrad(OP_CONV_WGRAD, nm + ".wgrad", geom_conv_wgrad(d), x_in, g_cur, i);
         if (unpool) {
             Op& wgop = p->ops.back();
             wgop.unpool = true;
             wgop.t3 = pool_am[i];
-            wgop.name = nm + ".unpool+wgrad";
+            wgop.name = nm + (wgop.fuse_sgd ? ".unpool+wgrad+sgd" : ".unpool+wgrad");
             wgop.kernel = wgrad_kernel_name(wgop.wg, wgop.wp, true);
             wgop.bytes += 3.0 * pool_y_elems[i] - 2.0 * conv_y_elems[i];
         }
@@ -487,14 +506,35 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
     }
 
     // ---- update ----
+    // A weight gradient that applies its own update moves behind its layer's data gradient (the next data-gradient
+    // operation in the list), which reads the weights of this step; nothing in between touches its operands.
+    // (Walking the list from its end, a moved operation lands behind the cursor and is not met again.)
+    for (size_t i = p->ops.size(); i-- > 0;) {
+        if (!p->ops[i].fuse_sgd) continue;
+        size_t j = i + 1;
+        while (j < p->ops.size() && p->ops[j].kind != OP_FC_DX && p->ops[j].kind != OP_CONV_DGRAD) ++j;
+        if (j == p->ops.size()) continue;  // first layer: no data gradient
+        std::rotate(p->ops.begin() + i, p->ops.begin() + i + 1, p->ops.begin() + j + 1);
+    }
+    // the remaining parameters (gradients stored by their kernels, biases) are updated by one pass per gap
     {
-        Op op;
-        op.kind = OP_SGD; op.name = "sgd";
-        op.n = np;
-        op.t0 = p->w32_off; op.t1 = p->dw_off; op.t2 = p->wb_off;
-        op.kernel = "sgd_kernel";
-        op.bytes = 14.0 * np;
-        p->ops.push_back(op);
+        std::sort(fused_ranges.begin(), fused_ranges.end());
+        fused_ranges.push_back({np, np});
+        size_t pos = 0;
+        int gaps = 0;
+        for (const auto& fr : fused_ranges) {
+            if (fr.first > pos) {
+                Op op;
+                op.kind = OP_SGD; op.name = gaps == 0 ? "sgd" : "sgd." + std::to_string(gaps);
+                op.n = fr.first - pos;
+                op.t0 = p->w32_off + pos * 4; op.t1 = p->dw_off + pos * 4; op.t2 = p->wb_off + pos * 2;
+                op.kernel = "sgd_kernel";
+                op.bytes = 14.0 * op.n;
+                p->ops.push_back(op);
+                ++gaps;
+            }
+            if (fr.second > pos) pos = fr.second;
+        }
     }
     if (p->packjobs.n > 0) {
         Op op;

@@ -38,6 +38,31 @@ constexpr double kPeakHbmGBs = 8000.0;
 constexpr int kNumCU = 256;
 constexpr int kNumXCD = 8;
 
+// ---- SGD update fused into the kernel that produces a weight gradient ----
+// Instead of storing dW, the producer applies w32 <- w32 - lr * dW to the fp32 master weights and re-derives the
+// bf16 compute copy, element for element what sgd_kernel does with a stored gradient (same fused multiply-add,
+// same rounding), so both routes give the same bits.
+struct SgdFuse {
+    float* w32;
+    bf16_t* wb;
+    float lr;
+};
+__device__ __forceinline__ float sgd_apply(float w, float g, float lr) { return __builtin_fmaf(-lr, g, w); }
+// one 16-byte group of parameters (old values in `a`): write the updated master weights and four bf16 values
+__device__ __forceinline__ void sgd_store4(float* w32, bf16_t* wb, float4 a, float lr, float g0, float g1, float g2,
+                                           float g3) {
+    a.x = sgd_apply(a.x, g0, lr); a.y = sgd_apply(a.y, g1, lr); a.z = sgd_apply(a.z, g2, lr); a.w = sgd_apply(a.w, g3, lr);
+    *reinterpret_cast<float4*>(w32) = a;
+    __bf16 b0 = (__bf16)a.x, b1 = (__bf16)a.y, b2 = (__bf16)a.z, b3 = (__bf16)a.w;
+    uint2 pk;
+    pk.x = (unsigned)__builtin_bit_cast(unsigned short, b0) | ((unsigned)__builtin_bit_cast(unsigned short, b1) << 16);
+    pk.y = (unsigned)__builtin_bit_cast(unsigned short, b2) | ((unsigned)__builtin_bit_cast(unsigned short, b3) << 16);
+    *reinterpret_cast<uint2*>(wb) = pk;
+}
+__device__ __forceinline__ void sgd_apply4(float* w32, bf16_t* wb, float lr, float g0, float g1, float g2, float g3) {
+    sgd_store4(w32, wb, *reinterpret_cast<const float4*>(w32), lr, g0, g1, g2, g3);
+}
+
 // ---- test hook: force a tile configuration / split count (-1 = choose from the shape) ----
 extern int g_force_fwd_cfg, g_force_wgrad_cfg, g_force_nsplit;
 
@@ -97,9 +122,13 @@ struct WgradPlan {
 WgradPlan plan_wgrad(const WgradGeom& g);
 // unpool_am: dy is the gradient of the 2x2 / stride-2 max-pooled output (N x P/2 x Q/2 x K) and unpool_am the pool's
 // argmax; only where wgrad_fuses_unpool() says so.
+// sgd: apply the update to the parameters instead of storing dW (dw may then be NULL); only where wgrad_fuses_sgd()
+// says so.
 int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
-                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid = nullptr, const uint8_t* unpool_am = nullptr);
+                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid = nullptr, const uint8_t* unpool_am = nullptr,
+                 const SgdFuse* sgd = nullptr);
 bool wgrad_fuses_unpool(const WgradGeom& g, const WgradPlan& plan);
+bool wgrad_fuses_sgd(const WgradGeom& g, const WgradPlan& plan);
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan, bool unpool);
 
 // stride-1 3x3 weight gradient with the input patch resident in LDS (wgrad_patch.hip)
@@ -162,7 +191,9 @@ const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan);
 // split-reduction epilogues (fixed summation order)
 int launch_reduce_bf16(const float* part, int nsplit, size_t elems, int ncols, const float* bias,
                        bool relu, bf16_t* out, hipStream_t st);
-int launch_reduce_f32(const float* part, int nsplit, size_t elems, float* out, hipStream_t st);
+// with `sgd`, the sums update the parameters (see SgdFuse) instead of being stored; `out` is then unused
+int launch_reduce_f32(const float* part, int nsplit, size_t elems, float* out, hipStream_t st,
+                      const SgdFuse* sgd = nullptr);
 
 // fill helpers used by the profiler
 int launch_fill_bf16(bf16_t* p, size_t n, uint32_t seed, hipStream_t st);

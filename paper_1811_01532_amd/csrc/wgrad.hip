@@ -26,6 +26,7 @@ struct WArgs {
     int Kred, Mred;
     int tiles_c, tiles_k, nsplit, ktiles, ktiles_per_split;
     FastDiv dPQ, dQ;
+    SgdFuse sgd;  // w32 != NULL (unsplit reduction, Kred % 4 == 0 only): update the parameters instead of storing dW
 };
 
 __device__ __forceinline__ int xcd_remap(int bid, int total) {
@@ -212,6 +213,58 @@ __global__ __launch_bounds__(64 * WAVES_C * WAVES_K) void wgrad_kernel(const WAr
 
     const bool vec4 = (a.Kred & 3) == 0;
     float* outp = a.out + (size_t)split * g.K * a.Kred;
+    if (vec4) {
+        // A lane of the MFMA accumulator holds 16-byte groups of 32 different output rows, so a direct store touches
+        // 32 rows per instruction.  Each wave instead turns its 32 x 64 blocks around in a private LDS region (the
+        // operand tiles are dead: the main loop ended with a barrier) and moves 256-byte row segments per 16 lanes.
+        // With a parameter block the old master weights are fetched before the block goes through LDS.
+        static_assert(FC % 2 == 0, "the epilogue stages 64 columns at a time");
+        constexpr int EP_PITCH = 64 * 4 + 16;  // rows 16 bytes apart modulo the bank width: both phases conflict-free
+        static_assert((NT / 64) * 32 * EP_PITCH <= 2 * STAGE, "epilogue staging does not fit the operand tiles");
+        unsigned char* const ep = smem + wave * (32 * EP_PITCH);
+        const int r_rd = lane >> 4, c_rd = (lane & 15) * 4;
+        const bool fused = a.sgd.w32 != nullptr;
+#pragma unroll
+        for (int j = 0; j < FK; ++j) {
+#pragma unroll
+            for (int ih = 0; ih < FC / 2; ++ih) {
+                const int col = col0 + wc * WC + ih * 64 + c_rd;
+                const int row0 = ko0 + wk * WK + j * 32 + r_rd;
+                float4 old[8];
+                if (fused) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const int ko = row0 + t * 4;
+                        old[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (ko < g.K && col < a.Kred)
+                            old[t] = *reinterpret_cast<const float4*>(a.sgd.w32 + (size_t)ko * a.Kred + col);
+                    }
+                }
+#pragma unroll
+                for (int ii = 0; ii < 2; ++ii) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int i = ih * 2 + ii;
+                        *reinterpret_cast<float4*>(ep + (lane & 31) * EP_PITCH + (ii * 32 + q * 8 + (lane >> 5) * 4) * 4) =
+                            make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2],
+                                        acc[i][j][q * 4 + 3]);
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();  // LDS operations of one wave complete in order
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const int ko = row0 + t * 4;
+                    const float4 v = *reinterpret_cast<const float4*>(ep + (t * 4 + r_rd) * EP_PITCH + c_rd * 4);
+                    if (ko >= g.K || col >= a.Kred) continue;
+                    const size_t e = (size_t)ko * a.Kred + col;
+                    if (fused) sgd_store4(a.sgd.w32 + e, a.sgd.wb + e, old[t], a.sgd.lr, v.x, v.y, v.z, v.w);
+                    else *reinterpret_cast<float4*>(outp + e) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < FK; ++j) {
         const int ko = ko0 + wk * WK + j * 32 + (lane & 31);
@@ -221,16 +274,9 @@ __global__ __launch_bounds__(64 * WAVES_C * WAVES_K) void wgrad_kernel(const WAr
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int col = col0 + wc * WC + i * 32 + q * 8 + (lane >> 5) * 4;
-                if (col >= a.Kred) continue;
-                float* o = outp + (size_t)ko * a.Kred + col;
-                if (vec4) {
-                    *reinterpret_cast<float4*>(o) = make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1],
-                                                                acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-                } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (col + e < a.Kred) o[e] = acc[i][j][q * 4 + e];
-                }
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < a.Kred) outp[(size_t)ko * a.Kred + col + e] = acc[i][j][q * 4 + e];
             }
         }
     }
@@ -274,8 +320,12 @@ WgradPlan plan_wgrad(const WgradGeom& g) {
     int cfg;
     if (mode != 0) cfg = 1;
     else if (g.K <= 64) cfg = 2;
-    else if (g.K >= 192 && Kred >= 256) cfg = 0;
-    else cfg = 1;
+    else if (g.K >= 192 && Kred >= 256) {
+        // A short reduction over a large output (the FC layers at training minibatches) is bound by the epilogue's
+        // stores: smaller tiles put several work-groups on a CU, whose store phases then overlap.
+        const long small_tiles = (long)((Kred + 127) / 128) * ((g.K + 127) / 128);
+        cfg = (Mred <= 256 && small_tiles >= 4L * kNumCU) ? 1 : 0;
+    } else cfg = 1;
     if (g_force_wgrad_cfg >= 0 && g_force_wgrad_cfg < 3 && (mode == 0 || g_force_wgrad_cfg == 1)) cfg = g_force_wgrad_cfg;
     if ((g_force_wgrad_cfg < 0 || g_force_wgrad_cfg == 4) && wgrad_c3_supported(g)) {
         p.cfg = 4;
@@ -310,10 +360,15 @@ WgradPlan plan_wgrad(const WgradGeom& g) {
 }
 
 int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, const bf16_t* dy,
-                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid, const uint8_t* unpool_am) {
+                 float* dw, void* ws, hipStream_t st, hipEvent_t ev_mid, const uint8_t* unpool_am,
+                 const SgdFuse* sgd) {
     if (unpool_am && !wgrad_fuses_unpool(g, plan))
         return set_error(WAP_EINVAL, "internal: fused max-pool backward not available for this weight gradient");
+    if (sgd && !wgrad_fuses_sgd(g, plan))
+        return set_error(WAP_EINVAL, "internal: fused SGD update not available for this weight gradient");
     WArgs wa;
+    wa.sgd = SgdFuse{nullptr, nullptr, 0.f};
+    if (sgd && plan.nsplit == 1) wa.sgd = *sgd;  // split reductions apply the update in the reduction kernel
     wa.x = x;
     wa.dy = dy;
     wa.g = g;
@@ -332,14 +387,14 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
         int rc4 = launch_wgrad_c3(g, plan.nsplit, x, dy, reinterpret_cast<float*>(ws), st);
         if (rc4 != WAP_OK) return rc4;
         if (ev_mid) (void)hipEventRecord(ev_mid, st);
-        return launch_reduce_f32(reinterpret_cast<const float*>(ws), plan.nsplit, (size_t)g.K * wa.Kred, dw, st);
+        return launch_reduce_f32(reinterpret_cast<const float*>(ws), plan.nsplit, (size_t)g.K * wa.Kred, dw, st, sgd);
     }
     if (plan.cfg == 3) {
         int rc3 = launch_wgrad_patch(g, plan.nsplit, x, dy, wa.out, st, unpool_am);
         if (rc3 != WAP_OK) return rc3;
         if (ev_mid) (void)hipEventRecord(ev_mid, st);
         if (plan.nsplit > 1)
-            return launch_reduce_f32(reinterpret_cast<const float*>(ws), plan.nsplit, (size_t)g.K * wa.Kred, dw, st);
+            return launch_reduce_f32(reinterpret_cast<const float*>(ws), plan.nsplit, (size_t)g.K * wa.Kred, dw, st, sgd);
         return WAP_OK;
     }
     size_t smem = smem_bytes(c);
@@ -358,7 +413,7 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
     if (ev_mid) (void)hipEventRecord(ev_mid, st);
     if (plan.nsplit > 1)
         return launch_reduce_f32(reinterpret_cast<const float*>(ws), plan.nsplit,
-                                 (size_t)g.K * wa.Kred, dw, st);
+                                 (size_t)g.K * wa.Kred, dw, st, sgd);
     return WAP_OK;
 }
 
@@ -367,6 +422,13 @@ int launch_wgrad(const WgradGeom& g, const WgradPlan& plan, const bf16_t* x, con
 namespace wap {
 bool wgrad_fuses_unpool(const WgradGeom& g, const WgradPlan& plan) {
     return plan.cfg == 3 && wgrad_patch_fuses_unpool(g);
+}
+// The update rides on whichever kernel holds the finished sums: the reduction kernel of a split product (the
+// first-layer kernels always reduce), or the epilogue of an unsplit generic product whose accumulator rows are
+// 16-byte groups of parameters.
+bool wgrad_fuses_sgd(const WgradGeom& g, const WgradPlan& plan) {
+    if (plan.cfg == 4 || plan.nsplit > 1) return true;
+    return plan.cfg < 3 && ((g.R * g.S * g.C) & 3) == 0;
 }
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan) { return wgrad_kernel_name(g, plan, false); }
 const char* wgrad_kernel_name(const WgradGeom& g, const WgradPlan& plan, bool unpool) {

@@ -159,3 +159,36 @@ def test_pool2x2_backward_entry_points_validate_on_the_host(wap):
     assert not wap.wap_conv2d_bwd_pool2x2_fused(small, wap.WAP_PASS_BWD_WEIGHT)
     if wap.wap_conv2d_workspace_bytes(small, wap.WAP_PASS_BWD_DATA) == 0:
         _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_data_pool2x2, small, 4096, 4096, 4096, None, 4096, None, None, s)
+
+
+def test_fused_update_entry_points_and_launch_list_order(wap):
+    """Host logic of the weight gradient that applies its own SGD update: argument checks, which shapes fuse, and
+    that in a launch list such an operation runs after the data gradient that still needs the old weights."""
+    s = 0
+    d = wap.conv_desc(2, 16, 16, 64, 64, 3, 3, 1, 1)
+    assert wap.wap_conv2d_bwd_weight_sgd_fused(d)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_weight_sgd, d, 4096, 4096, None, 4096, 0.01, None, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_weight_sgd, d, 4096, 4096, 4096, None, 0.01, None, None, s)
+    _expect(wap, wap.WAP_EINVAL, wap.wap_conv2d_bwd_weight_sgd, d, 4096, 4096, 4096 + 4, 4096, 0.01, None, None, s)
+    f = wap.fc_desc(16, 2050, 2048)          # rows of 2050 parameters: no 16-byte groups per accumulator row
+    assert not wap.wap_fc_bwd_weight_sgd_fused(f)
+    assert wap.wap_fc_bwd_weight_sgd_fused(wap.fc_desc(64, 25088, 4096))
+    if wap.wap_fc_workspace_bytes(f, wap.WAP_PASS_BWD_WEIGHT) == 0:
+        _expect(wap, wap.WAP_EINVAL, wap.wap_fc_bwd_weight_sgd, f, 4096, 4096, 4096, 4096, 0.01, None, None, s)
+    for net, flags in (("vgg16", 0), ("alexnet", 0), ("alexnet", wap.WAP_STEP_BIAS), ("vgg16", wap.WAP_STEP_KEEP_GRADS)):
+        names = [o[0] for o in wap.StepPlan(net, 32, flags=flags).ops()]
+        fused = [n for n in names if n.endswith("+sgd")]
+        if flags & wap.WAP_STEP_KEEP_GRADS:
+            assert not fused and names.count("sgd") == 1
+            continue
+        assert fused, net
+        for n in fused:
+            layer = n.split(".")[0]
+            later = [m for m in names[names.index(n) + 1:]
+                     if m.startswith(layer + ".") and ("dgrad" in m or ".dx" in m)]
+            assert not later, (n, later)     # the layer's data gradient reads this step's weights: it runs first
+        # a layer is updated either by its gradient kernel or by a separate pass, and biases always by a pass
+        n_layers = 8 if net == "alexnet" else 16
+        assert len(set(fused)) == len(fused) <= n_layers
+        if len(fused) < n_layers or (flags & wap.WAP_STEP_BIAS):
+            assert any(m == "sgd" for m in names)

@@ -163,6 +163,23 @@ def test_conv_three_passes_match_oracle(orc, name, shape, force):
         wap.wap_conv2d_bwd_weight(d, xd, gd, dw2, ws)
         torch.cuda.synchronize()
         assert torch.equal(dw, dw2)
+        # ---- weight gradient with the SGD update applied by the kernel that finishes it: against the oracle's
+        # gradient followed by its update, and bit for bit against the device's own two-call chain ----
+        lr = 0.05
+        w32_0 = (si.rng(100 + ci, 6).standard_normal((K, R, S, C)) * 0.05).astype(np.float32)
+        wm, wm2 = torch.from_numpy(w32_0).cuda(), torch.from_numpy(w32_0).cuda()
+        wbf = torch.full((K, R, S, C), float("nan"), dtype=torch.bfloat16, device="cuda")
+        wbf2 = torch.full((K, R, S, C), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dws = None if wap.wap_conv2d_bwd_weight_sgd_fused(d) else torch.empty_like(dw)
+        wap.wap_conv2d_bwd_weight_sgd(d, xd, gd, wm, wbf, lr, dws, ws)
+        wap.wap_sgd_update(K * R * S * C, wm2, dw, lr, wbf2)
+        torch.cuda.synchronize()
+        assert torch.equal(wm, wm2) and torch.equal(wbf.view(torch.int16), wbf2.view(torch.int16)), "wgrad+sgd vs two calls"
+        lr32 = float(np.float32(lr))
+        refw = orc.sgd(w32_0.astype(np.float64), refdw, lr32)
+        bound = gu.TOL_F32_OUT * lr32 * np.max(np.abs(refdw)) + 2.0 ** -22 * np.max(np.abs(refw))
+        assert np.max(np.abs(gu.host_f64(wm) - refw)) <= bound, "wgrad+sgd vs oracle"
+        assert np.array_equal(gu.host_f64(wbf), orc.round_bf16(gu.host_f64(wm))), "bf16 copy"
         # ---- both backward passes with dy given as the gradient of the 2x2 / stride-2 pooled output plus the pool's
         # argmax: against the oracle's max-pool backward followed by its data / weight gradient, and bit for bit
         # against the device's own unfused chain; where the loader routes the gradient itself, also without the

@@ -21,6 +21,10 @@ FC_CASES = [
     # model-parallel shards of the VGG-16 head: out_features / 8 at the full minibatch
     ("fc8_shard_125", 64, 4096, 125, (-1, -1, -1)),
     ("fc6_shard_512", 64, 25088, 512, (-1, -1, -1)),
+    # unsplit weight gradient (one tile per work-group, the update applied in its epilogue), and a row length
+    # that is not a multiple of four, where the update cannot ride on the gradient kernel
+    ("b64_4096_4096_unsplit", 64, 4096, 4096, (-1, -1, -1)),
+    ("b16_2050_2048_update_apart", 16, 2050, 2048, (-1, -1, -1)),
 ]
 
 
@@ -65,6 +69,28 @@ def test_fc_fwd_bwd_match_oracle(orc, name, B, n_in, n_out, force):
         wap.wap_fc_bwd(d, xd, None, gd, None, dW2, ws)
         torch.cuda.synchronize()
         assert torch.equal(dx, dx2) and torch.equal(dW, dW2)
+        # weight gradient with the SGD update applied by the kernel that finishes it: bit for bit the two-call
+        # chain, and the oracle's gradient followed by its update
+        lr = 0.05
+        w32_0 = (si.rng(200 + ci, 4).standard_normal((n_out, n_in)) * 0.05).astype(np.float32)
+        wm, wm2 = torch.from_numpy(w32_0).cuda(), torch.from_numpy(w32_0).cuda()
+        wbf = torch.full((n_out, n_in), float("nan"), dtype=torch.bfloat16, device="cuda")
+        wbf2 = torch.full((n_out, n_in), float("nan"), dtype=torch.bfloat16, device="cuda")
+        fused = wap.wap_fc_bwd_weight_sgd_fused(d)
+        assert fused == (name != "b16_2050_2048_update_apart")
+        wap.wap_fc_bwd_weight_sgd(d, xd, gd, wm, wbf, lr, None if fused else torch.empty_like(dW), ws)
+        wap.wap_sgd_update(n_out * n_in, wm2, dW, lr, wbf2)
+        torch.cuda.synchronize()
+        assert torch.equal(wm, wm2) and torch.equal(wbf.view(torch.int16), wbf2.view(torch.int16))
+        lr32 = float(np.float32(lr))
+        refdW = orc.fc_bwd_weight(g64, x64)
+        refw = orc.sgd(w32_0.astype(np.float64), refdW, lr32)
+        bound = gu.TOL_F32_OUT * lr32 * np.max(np.abs(refdW)) + 2.0 ** -22 * np.max(np.abs(refw))
+        assert np.max(np.abs(gu.host_f64(wm) - refw)) <= bound
+        assert np.array_equal(gu.host_f64(wbf), orc.round_bf16(gu.host_f64(wm)))
+        if not fused:
+            with pytest.raises(wap.WapError):
+                wap.wap_fc_bwd_weight_sgd(d, xd, gd, wm, wbf, lr, None, ws)
     finally:
         wap.lib().wap_debug_force(-1, -1, -1)
 

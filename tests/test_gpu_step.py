@@ -207,8 +207,9 @@ def test_step_every_operation_matches_oracle(orc, net, B, image, with_bias):
                                                 ("alexnet", 2, 224, 0), ("vgg16", 2, 64, 2), ("alexnet", 2, 131, 2)])
 def test_step_without_kept_gradients_is_bitwise_the_same(orc, net, B, image, extra):
     """The production plan (ping-pong gradient buffers, pool taken in the conv epilogue, pool backward routed in the
-    backward kernels' loaders, ReLU derivatives riding on data-gradient epilogues) gives the same gradients and loss
-    as the plan that keeps every intermediate, which the teacher-forced test checks against the oracle.  The larger
+    backward kernels' loaders, ReLU derivatives riding on data-gradient epilogues, SGD updates applied by the kernels
+    that finish the weight gradients) gives the same weights, stored gradients and loss as the plan that keeps every
+    intermediate, which the teacher-forced test checks against the oracle.  The larger
     images reach the fused paths the 32-pixel case is too small for.  With biases the bias gradient of a layer whose
     pool backward is routed in the loaders is summed over the pooled gradient instead of the full-size one: the same
     sum in another order, so after the first step those vectors agree to fp32 rounding and everything else bit for
@@ -223,20 +224,23 @@ def test_step_without_kept_gradients_is_bitwise_the_same(orc, net, B, image, ext
             plan.run(ar.buf)
         torch.cuda.synchronize()
         names = [k for k in weights if not k.endswith("#bias")]
-        nw = sum(ar.t[k + ".dw"][1] for k in names) // 4   # the weights come first in the parameter blocks
-        n = ar.t["params.dw"][1] // 4
-        res.append((ar.f32("params.dw", (n,)).clone(), ar.f32("params.w32", (n,)).clone(),
-                    ar.f32("loss", (4,))[0].item(), nw,
-                    {k: ar.f32(k + ".db", (weights[k].shape[0],)).clone() for k in names} if extra else {}))
-    nw = res[0][3]
-    assert nw <= res[0][0].numel() and (extra or nw > 0)
+        n = ar.t["params.w32"][1] // 4
+        # layers whose weight-gradient kernel applies the update itself never store their gradient
+        fused = {o[0].split(".")[0] for o in plan.ops() if o[0].endswith("+sgd")}
+        res.append(({k: ar.f32(k + ".dw", weights[k].shape).clone() for k in names if k not in fused},
+                    ar.f32("params.w32", (n,)).clone(), ar.f32("loss", (4,))[0].item(), fused,
+                    {k: ar.f32(k + ".db", (weights[k].shape[0],)).clone() for k in names} if extra else {},
+                    {k: ar.bf16(k + ".w", weights[k].shape).clone() for k in names}))
+    assert not res[0][3] and res[1][3], "the kept-gradients plan stores every gradient, the production plan fuses updates"
+    for k, v in res[1][0].items():
+        assert torch.equal(res[0][0][k], v), k + ".dw"
+    for k in res[0][5]:
+        assert torch.equal(res[0][5][k].view(torch.int16), res[1][5][k].view(torch.int16)), k + ".w (bf16 copy)"
     if not extra:
-        assert torch.equal(res[0][0], res[1][0])
-        assert torch.equal(res[0][1], res[1][1])
+        assert torch.equal(res[0][1], res[1][1])          # every master weight after two steps
     else:
-        # weight gradients (the leading part of the block, alignment gaps included) bit for bit, bias gradients close
-        last_w = max(ar.t[k + ".dw"][0] + ar.t[k + ".dw"][1] for k in names) - ar.t["params.dw"][0]
-        assert torch.equal(res[0][0][:last_w // 4], res[1][0][:last_w // 4])
+        # weights (the leading part of the block, alignment gaps included) bit for bit, bias gradients close
+        last_w = max(ar.t[k + ".w32"][0] + ar.t[k + ".w32"][1] for k in names) - ar.t["params.w32"][0]
         assert torch.equal(res[0][1][:last_w // 4], res[1][1][:last_w // 4])
         for k in names:
             a, b = res[0][4][k].double(), res[1][4][k].double()
