@@ -309,6 +309,20 @@ def main():
     del buf, plan
     torch.cuda.empty_cache()
 
+    # The same step in the form a replica of a data-parallel job runs (every weight gradient stored for the exchange,
+    # the update a separate pass): reported beside the headline, whose one-GPU job lets the gradient kernels update
+    # the weights themselves.
+    p2 = wap.StepPlan(net, B, lr=LR, image=image,
+                      flags=wap.WAP_STEP_STORE_GRADS | (wap.WAP_STEP_BIAS if a.bias else 0))
+    b2 = _arena(p2, torch)
+    init_step(p2, b2, net, B, image, torch, wap, "device")
+    sec2 = time_plain_steps(p2, b2, steps=a.steps, warmup=a.warmup, torch=torch)   # as the headline: the clock settles
+    out["gradients_stored"] = {"ms_per_step": sec2 * 1e3, "tflops": flops_step / sec2 / 1e12, "ops_per_step": p2.num_ops(),
+                               "note": "WAP_STEP_STORE_GRADS: dw of every layer written, SGD as a separate pass (a data-"
+                                       "parallel replica's share; not the headline)"}
+    del b2, p2
+    torch.cuda.empty_cache()
+
     md = []
     if not a.no_table:
         # ---- step-level utilisation versus per-GPU minibatch, both networks ----

@@ -264,9 +264,15 @@ typedef struct wap_step_plan wap_step_plan;
  * unfused (for inspection); WAP_STEP_BIAS gives every conv / FC layer an fp32 bias (tensors "<layer>.b32",
  * gradient "<layer>.db"): added in the forward epilogues, its gradient (column sums of the gradient w.r.t. the
  * layer's pre-activation output) computed by one extra operation per layer, updated by the same SGD launch.
- * Without the flag the layers have no bias, which is how the benchmark runs. */
+ * Without the flag the layers have no bias, which is how the benchmark runs.
+ * By default the kernel that finishes a layer's weight gradient applies the SGD update itself (the gradient
+ * tensor "<layer>.dw" is then not written): the form of a job on one GPU, where nothing else needs the
+ * gradient.  WAP_STEP_STORE_GRADS stores every weight gradient and updates in a separate pass at the end of
+ * the step instead: the form a replica of a data-parallel job needs, whose gradients are exchanged
+ * (Section 2.1) between the backward pass and the update. */
 #define WAP_STEP_KEEP_GRADS 1u
 #define WAP_STEP_BIAS 2u
+#define WAP_STEP_STORE_GRADS 4u
 int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, float lr, uint32_t flags,
                          wap_step_plan** out);
 void wap_step_plan_destroy(wap_step_plan* p);

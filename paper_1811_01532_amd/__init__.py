@@ -17,6 +17,7 @@ WAP_RELU = 1
 WAP_PASS_FWD, WAP_PASS_BWD_DATA, WAP_PASS_BWD_WEIGHT = 0, 1, 2
 WAP_STEP_KEEP_GRADS = 1
 WAP_STEP_BIAS = 2
+WAP_STEP_STORE_GRADS = 4
 
 PEAK_BF16_TFLOPS = 2516.6
 PEAK_HBM_GBS = 8000.0

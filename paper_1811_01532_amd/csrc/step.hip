@@ -163,7 +163,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
                          wap_step_plan** out) {
     if (!net || !out) return set_error(WAP_EINVAL, "step plan: NULL argument");
     if (minibatch < 1 || image < 1) return set_error(WAP_EINVAL, "step plan: minibatch and image must be >= 1");
-    if (flags & ~3u) return set_error(WAP_EINVAL, "step plan: unknown flag bits 0x%x", flags);
+    if (flags & ~7u) return set_error(WAP_EINVAL, "step plan: unknown flag bits 0x%x", flags);
     const ConvL* convs;
     int nconv;
     if (!strcmp(net, "alexnet")) { convs = kAlexConvs; nconv = 5; }
@@ -171,6 +171,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
     else return set_error(WAP_EINVAL, "step plan: unknown net '%s' (alexnet, vgg16)", net);
     const bool keep = (flags & WAP_STEP_KEEP_GRADS) != 0;
     const bool with_bias = (flags & WAP_STEP_BIAS) != 0;
+    const bool fuse_update = !keep && (flags & WAP_STEP_STORE_GRADS) == 0;
     const int B = minibatch;
 
     // ---- walk the geometry, validating every layer ----
@@ -326,7 +327,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         op.flops = 2.0 * g.N * g.P * g.Q * nw;
         op.bytes = 2.0 * ((double)g.N * g.H * g.W * g.C + (double)g.N * g.P * g.Q * g.K) + 4.0 * nw;
         op.t0 = x; op.t1 = dy; op.t2 = p->dw_off + poff[li] * 4;
-        if (!keep && (poff[li] & 3) == 0 && wgrad_fuses_sgd(g, op.wp)) {
+        if (fuse_update && (poff[li] & 3) == 0 && wgrad_fuses_sgd(g, op.wp)) {
             op.fuse_sgd = true;
             op.t6 = p->w32_off + poff[li] * 4;
             op.t7 = p->wb_off + poff[li] * 2;

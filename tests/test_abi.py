@@ -175,10 +175,11 @@ def test_fused_update_entry_points_and_launch_list_order(wap):
     assert wap.wap_fc_bwd_weight_sgd_fused(wap.fc_desc(64, 25088, 4096))
     if wap.wap_fc_workspace_bytes(f, wap.WAP_PASS_BWD_WEIGHT) == 0:
         _expect(wap, wap.WAP_EINVAL, wap.wap_fc_bwd_weight_sgd, f, 4096, 4096, 4096, 4096, 0.01, None, None, s)
-    for net, flags in (("vgg16", 0), ("alexnet", 0), ("alexnet", wap.WAP_STEP_BIAS), ("vgg16", wap.WAP_STEP_KEEP_GRADS)):
+    for net, flags in (("vgg16", 0), ("alexnet", 0), ("alexnet", wap.WAP_STEP_BIAS), ("vgg16", wap.WAP_STEP_KEEP_GRADS),
+                       ("alexnet", wap.WAP_STEP_STORE_GRADS)):
         names = [o[0] for o in wap.StepPlan(net, 32, flags=flags).ops()]
         fused = [n for n in names if n.endswith("+sgd")]
-        if flags & wap.WAP_STEP_KEEP_GRADS:
+        if flags & (wap.WAP_STEP_KEEP_GRADS | wap.WAP_STEP_STORE_GRADS):
             assert not fused and names.count("sgd") == 1
             continue
         assert fused, net

@@ -217,7 +217,9 @@ def test_step_without_kept_gradients_is_bitwise_the_same(orc, net, B, image, ext
     import paper_1811_01532_amd as wap
     res = []
     steps = 1 if extra else 2
-    for flags in (wap.WAP_STEP_KEEP_GRADS | extra, extra):  # extra = 2: with biases
+    # extra = 2: with biases; the third plan stores the weight gradients and updates in a separate pass (the form
+    # of a replica whose gradients are exchanged), everything else as in production
+    for flags in (wap.WAP_STEP_KEEP_GRADS | extra, extra, wap.WAP_STEP_STORE_GRADS | extra):
         plan, ar, shapes, fc_dims, weights, _, _ = _setup(net, B, image, flags, 501)
         print(f"[case] step {net} B={B} image={image} flags={flags} ops={[o[0] for o in plan.ops()] if not (flags & 1) else plan.num_ops()}", flush=True)
         for _ in range(steps):  # without biases: a second step on the updated weights
@@ -231,21 +233,24 @@ def test_step_without_kept_gradients_is_bitwise_the_same(orc, net, B, image, ext
                     ar.f32("params.w32", (n,)).clone(), ar.f32("loss", (4,))[0].item(), fused,
                     {k: ar.f32(k + ".db", (weights[k].shape[0],)).clone() for k in names} if extra else {},
                     {k: ar.bf16(k + ".w", weights[k].shape).clone() for k in names}))
-    assert not res[0][3] and res[1][3], "the kept-gradients plan stores every gradient, the production plan fuses updates"
-    for k, v in res[1][0].items():
-        assert torch.equal(res[0][0][k], v), k + ".dw"
-    for k in res[0][5]:
-        assert torch.equal(res[0][5][k].view(torch.int16), res[1][5][k].view(torch.int16)), k + ".w (bf16 copy)"
-    if not extra:
-        assert torch.equal(res[0][1], res[1][1])          # every master weight after two steps
-    else:
-        # weights (the leading part of the block, alignment gaps included) bit for bit, bias gradients close
-        last_w = max(ar.t[k + ".w32"][0] + ar.t[k + ".w32"][1] for k in names) - ar.t["params.w32"][0]
-        assert torch.equal(res[0][1][:last_w // 4], res[1][1][:last_w // 4])
-        for k in names:
-            a, b = res[0][4][k].double(), res[1][4][k].double()
-            scale = max(float(a.abs().max()), 1e-30)
-            assert float((a - b).abs().max()) <= 1e-5 * scale, f"{k}.db differs by more than fp32 summation order"
+    assert not res[0][3] and res[1][3] and not res[2][3], "only the production plan fuses updates"
+    assert set(res[2][0]) == set(res[0][0])
+    for r in res[1:]:
+        for k, v in r[0].items():
+            assert torch.equal(res[0][0][k], v), k + ".dw"
+        for k in res[0][5]:
+            assert torch.equal(res[0][5][k].view(torch.int16), r[5][k].view(torch.int16)), k + ".w (bf16 copy)"
+        if not extra:
+            assert torch.equal(res[0][1], r[1])          # every master weight after two steps
+        else:
+            # weights (the leading part of the block, alignment gaps included) bit for bit, bias gradients close
+            last_w = max(ar.t[k + ".w32"][0] + ar.t[k + ".w32"][1] for k in names) - ar.t["params.w32"][0]
+            assert torch.equal(res[0][1][:last_w // 4], r[1][:last_w // 4])
+            for k in names:
+                a, b = res[0][4][k].double(), r[4][k].double()
+                scale = max(float(a.abs().max()), 1e-30)
+                assert float((a - b).abs().max()) <= 1e-5 * scale, f"{k}.db differs by more than fp32 summation order"
+        assert res[0][2] == r[2]
     assert res[0][2] == res[1][2]
     assert np.isfinite(res[0][2])
 
