@@ -124,6 +124,23 @@ def test_fc_layer_full_size_sampled(orc, name, B, n_in, n_out):
     ref = orc.fc_bwd_weight(np.ascontiguousarray(g64[:, cols]), np.ascontiguousarray(x64[:, icols]))
     e = gu.rel_err(gu.host_f64(dW)[np.ix_(cols, icols)], ref)
     assert e <= gu.TOL and e <= gu.TOL_F32_OUT, f"{name} dW rel err {e}"
+    # the weight gradient that applies the SGD update itself (the form the launch list runs): bit for bit the
+    # separate update with the gradient above, and the sampled weights against oracle gradient + oracle update
+    lr = 0.05
+    w0 = (torch.randn((n_out, n_in), device="cuda", generator=torch.Generator(device="cuda").manual_seed(652)) * 0.05)
+    wm, wm2 = w0.clone(), w0.clone()
+    wbf = torch.empty((n_out, n_in), dtype=torch.bfloat16, device="cuda")
+    wbf2 = torch.empty((n_out, n_in), dtype=torch.bfloat16, device="cuda")
+    assert wap.wap_fc_bwd_weight_sgd_fused(d)
+    wap.wap_fc_bwd_weight_sgd(d, xd, gd, wm, wbf, lr, None, ws)
+    wap.wap_sgd_update(n_out * n_in, wm2, dW, lr, wbf2)
+    torch.cuda.synchronize()
+    assert torch.equal(wm, wm2) and torch.equal(wbf.view(torch.int16), wbf2.view(torch.int16)), name + " dW+sgd"
+    w0s = w0[torch.from_numpy(cols).cuda()][:, torch.from_numpy(icols).cuda()].double().cpu().numpy()
+    refw = orc.sgd(w0s, ref, float(np.float32(lr)))
+    gots = wm[torch.from_numpy(cols).cuda()][:, torch.from_numpy(icols).cuda()].double().cpu().numpy()
+    bound = gu.TOL_F32_OUT * float(np.float32(lr)) * np.max(np.abs(ref)) + 2.0 ** -22 * np.max(np.abs(refw))
+    assert np.max(np.abs(gots - refw)) <= bound, name + " dW+sgd vs oracle"
 
 
 # VGG-16 layers that are followed by a 2x2 pool, at per-GPU minibatch 64: name, N, H, C, K
