@@ -8,8 +8,10 @@
 // with ds_read_b64_tr_b16.  The reduction is split across work-groups (the output is tiny, the
 // reduction is N*P*Q long); every split writes an fp32 partial tile and a second kernel adds the
 // partials in split order, so results are bitwise reproducible.  The x-column fragment is the MFMA
-// "A" operand: each lane then owns 4 consecutive (r,s,c) columns of one output channel, i.e. one
-// 16-byte fp32 store.
+// "A" operand: each lane then owns 4 consecutive (r,s,c) columns of one output channel; the epilogue
+// turns each wavefront's blocks around in LDS so that 16 lanes store one 256-byte run of a row.  With
+// a parameter block the epilogue (or the reduction kernel of a split product) applies the SGD update
+// with the finished sums instead of storing them.
 #include "wap_internal.h"
 
 namespace wap {
