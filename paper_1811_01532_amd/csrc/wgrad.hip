@@ -326,7 +326,7 @@ WgradPlan plan_wgrad(const WgradGeom& g) {
         // A short reduction over a large output (the FC layers at training minibatches) is bound by the epilogue's
         // stores: smaller tiles put several work-groups on a CU, whose store phases then overlap.
         const long small_tiles = (long)((Kred + 127) / 128) * ((g.K + 127) / 128);
-        cfg = (Mred <= 256 && small_tiles >= 4L * kNumCU) ? 1 : 0;
+        cfg = (Mred <= 256 && small_tiles >= kNumCU) ? 1 : 0;
     } else cfg = 1;
     if (g_force_wgrad_cfg >= 0 && g_force_wgrad_cfg < 3 && (mode == 0 || g_force_wgrad_cfg == 1)) cfg = g_force_wgrad_cfg;
     if ((g_force_wgrad_cfg < 0 || g_force_wgrad_cfg == 4) && wgrad_c3_supported(g)) {
