@@ -343,9 +343,10 @@ class StepPlan:
     def graph_launch(self, stream):
         _check(lib().wap_step_graph_launch(self._p, _stream(stream)))
 
-    def time(self, arena, steps=1, stream=None, op_mask=None, with_prologue=False):
-        """`steps` steps with events around every operation (or only those whose op_mask entry is true):
-        (main-kernel us, epilogue-kernel us) lists, plus the weight-repacking-kernel us list on request."""
+    def time(self, arena, steps=1, stream=None, op_mask=None, with_prologue=False, every=1):
+        """`steps` steps with events around every operation (or only those whose op_mask entry is true), in every
+        `every`-th step: (main-kernel us, epilogue-kernel us) lists, plus the weight-repacking-kernel us list on
+        request."""
         n = self.num_ops()
         us = (ctypes.c_float * n)()
         epi = (ctypes.c_float * n)()
@@ -355,8 +356,8 @@ class StepPlan:
             if len(op_mask) != n:
                 raise ValueError("op_mask needs one entry per operation")
             mask = (ctypes.c_uint8 * n)(*[1 if m else 0 for m in op_mask])
-        _check(lib().wap_step_time_masked(self._p, _ptr(arena), ctypes.c_size_t(_nbytes(arena)), _stream(stream),
-                                          int(steps), mask, us, epi, pro))
+        _check(lib().wap_step_time_sampled(self._p, _ptr(arena), ctypes.c_size_t(_nbytes(arena)), _stream(stream),
+                                           int(steps), int(every), mask, us, epi, pro))
         if with_prologue:
             return ([float(us[i]) for i in range(n)], [float(epi[i]) for i in range(n)],
                     [float(pro[i]) for i in range(n)])

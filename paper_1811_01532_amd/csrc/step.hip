@@ -658,13 +658,21 @@ int wap_step_time(const wap_step_plan* p, void* arena, size_t arena_bytes, void*
 
 int wap_step_time_masked(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
                          const uint8_t* op_mask, float* us_out, float* us_epilogue_out, float* us_prologue_out) {
+    return wap_step_time_sampled(p, arena, arena_bytes, stream, steps, 1, op_mask, us_out, us_epilogue_out,
+                                 us_prologue_out);
+}
+
+int wap_step_time_sampled(const wap_step_plan* p, void* arena, size_t arena_bytes, void* stream, int32_t steps,
+                          int32_t every, const uint8_t* op_mask, float* us_out, float* us_epilogue_out,
+                          float* us_prologue_out) {
     int rc = check_arena(p, arena, arena_bytes);
     if (rc != WAP_OK) return rc;
-    if (!us_out || !us_epilogue_out || steps < 1) return set_error(WAP_EINVAL, "step: bad argument");
+    if (!us_out || !us_epilogue_out || steps < 1 || every < 1) return set_error(WAP_EINVAL, "step: bad argument");
+    const int timed = (steps + every - 1) / every;  // steps 0, every, 2 * every, ... carry the events
     unsigned char* base = (unsigned char*)arena;
     hipStream_t st = (hipStream_t)stream;
     const size_t n = p->ops.size();
-    const size_t need = 4 * n * (size_t)steps;
+    const size_t need = 4 * n * (size_t)timed;
     while (p->events.size() < need) {
         hipEvent_t e;
         if (hipEventCreate(&e) != hipSuccess) return set_error(WAP_EHIP, "hipEventCreate failed");
@@ -686,8 +694,8 @@ int wap_step_time_masked(const wap_step_plan* p, void* arena, size_t arena_bytes
     };
     for (int s = 0; s < steps && rc == WAP_OK; ++s)
         for (size_t i = 0; i < n && rc == WAP_OK; ++i) {
-            hipEvent_t* ev = &p->events[4 * ((size_t)s * n + i)];
-            if (op_mask && !op_mask[i]) {
+            hipEvent_t* ev = &p->events[4 * ((size_t)(s / every) * n + i)];
+            if ((s % every) != 0 || (op_mask && !op_mask[i])) {
                 rc = run_op(p, p->ops[i], base, st, nullptr);
                 continue;
             }
@@ -710,7 +718,7 @@ int wap_step_time_masked(const wap_step_plan* p, void* arena, size_t arena_bytes
         }
         const bool pro = has_prologue(p->ops[i]);
         double sum_pro = 0;
-        for (int s = 0; s < steps; ++s) {
+        for (int s = 0; s < timed; ++s) {
             float ms = 0.f;
             hipEvent_t* ev = &p->events[4 * ((size_t)s * n + i)];
             hipEvent_t first = ev[0];
@@ -729,9 +737,9 @@ int wap_step_time_masked(const wap_step_plan* p, void* arena, size_t arena_bytes
                 sum += ms;
             }
         }
-        if (us_prologue_out) us_prologue_out[i] = (float)(sum_pro * 1000.0 / steps);
-        us_out[i] = (float)(sum * 1000.0 / steps);
-        us_epilogue_out[i] = (float)(sum_epi * 1000.0 / steps);
+        if (us_prologue_out) us_prologue_out[i] = (float)(sum_pro * 1000.0 / timed);
+        us_out[i] = (float)(sum * 1000.0 / timed);
+        us_epilogue_out[i] = (float)(sum_epi * 1000.0 / timed);
     }
     return WAP_OK;
 }

@@ -293,3 +293,34 @@ def test_step_graph_replays_match_eager_steps(orc, net, B, image):
             side.synchronize()
             assert same(ar.buf, refs[k]), f"replay round {rep}, step {k} differs from the eager step"
         assert np.isfinite(float(scratch))
+
+
+def test_step_timing_entry_points_do_the_same_work(orc):
+    """wap_step_time / _masked / _sampled run the launch list exactly as wap_step_run does (the arena ends bitwise
+    equal) and report a positive duration for every bracketed operation and zero for the others."""
+    import paper_1811_01532_amd as wap
+    plan, ar, *_ = _setup("vgg16", 2, 64, 0, 530)
+    print("[case] step timing entry points", flush=True)
+    start = ar.buf.clone()
+    for _ in range(4):
+        plan.run(ar.buf)
+    torch.cuda.synchronize()
+    ref = ar.buf.clone()
+    ws_off, ws_nb = ar.t["workspace"]
+
+    def same(a, b):
+        return torch.equal(a[:ws_off], b[:ws_off]) and torch.equal(a[ws_off + ws_nb:], b[ws_off + ws_nb:])
+
+    ops = plan.ops()
+    mask = [o[0].endswith(".fwd") or ".fwd+" in o[0] for o in ops]
+    assert any(mask) and not all(mask)
+    ar.buf.copy_(start)
+    us, epi = plan.time(ar.buf, steps=4, op_mask=mask, every=2)      # events in steps 0 and 2
+    assert same(ar.buf, ref)
+    assert all((u > 0) == m for u, m in zip(us, mask)), list(zip([o[0] for o in ops], us))
+    ar.buf.copy_(start)
+    us, epi, pro = plan.time(ar.buf, steps=4, with_prologue=True)    # every operation, every step
+    assert same(ar.buf, ref)
+    assert all(u > 0 for u in us) and all(e >= 0 for e in epi) and all(q >= 0 for q in pro)
+    with pytest.raises(wap.WapError):
+        plan.time(ar.buf, steps=4, every=0)
