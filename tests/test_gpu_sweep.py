@@ -57,6 +57,16 @@ def test_random_conv_shapes_match_oracle(orc, seed, ncase):
              gu.rel_err(gu.host_f64(dx), orc.conv2d_bwd_data(g64, w64, (N, H, W, C), st, pad)),
              gu.rel_err(gu.host_f64(dw), orc.conv2d_bwd_weight(x64, g64, (K, R, S, C), st, pad))]
         ok = e[0] <= gu.TOL_BF16_OUT and e[1] <= gu.TOL_BF16_OUT and e[2] <= gu.TOL_F32_OUT
+        # the weight gradient with the update applied by its own kernels: bit for bit gradient + separate update
+        # (the gradient itself was checked against the oracle above)
+        w0 = (torch.randn((K, R, S, C), device="cuda", generator=torch.Generator(device="cuda").manual_seed(ci)) * 0.05)
+        wm, wm2 = w0.clone(), w0.clone()
+        wbf, wbf2 = torch.empty_like(wm, dtype=torch.bfloat16), torch.empty_like(wm, dtype=torch.bfloat16)
+        scr = None if wap.wap_conv2d_bwd_weight_sgd_fused(d) else torch.empty_like(dw)
+        wap.wap_conv2d_bwd_weight_sgd(d, xd, gd, wm, wbf, 0.05, scr, ws)
+        wap.wap_sgd_update(K * R * S * C, wm2, dw, 0.05, wbf2)
+        torch.cuda.synchronize()
+        ok = ok and torch.equal(wm, wm2) and torch.equal(wbf.view(torch.int16), wbf2.view(torch.int16))
         if P % 2 == 0 and Q % 2 == 0:
             gpb = si.normal_bf16(si.rng(9000 + 100 * seed + ci, 4), (N, P // 2, Q // 2, K))
             amh = si.rng(9000 + 100 * seed + ci, 5).integers(0, 4, size=(N, P // 2, Q // 2, K), dtype=np.uint8)
@@ -106,6 +116,14 @@ def test_random_fc_shapes_match_oracle(orc):
         e = [gu.rel_err(gu.host_f64(y), orc.fc_fwd(x64, W64, bias=bias.astype(np.float64), relu=True)),
              gu.rel_err(gu.host_f64(dx), orc.fc_bwd_data(g64, W64)),
              gu.rel_err(gu.host_f64(dW), orc.fc_bwd_weight(g64, x64))]
-        if not (e[0] <= gu.TOL_BF16_OUT and e[1] <= gu.TOL_BF16_OUT and e[2] <= gu.TOL_F32_OUT):
-            bad.append(((B, n_in, n_out), [f"{v:.2e}" for v in e]))
+        w0 = (torch.randn((n_out, n_in), device="cuda", generator=torch.Generator(device="cuda").manual_seed(ci)) * 0.05)
+        wm, wm2 = w0.clone(), w0.clone()
+        wbf, wbf2 = torch.empty_like(wm, dtype=torch.bfloat16), torch.empty_like(wm, dtype=torch.bfloat16)
+        scr = None if wap.wap_fc_bwd_weight_sgd_fused(d) else torch.empty_like(dW)
+        wap.wap_fc_bwd_weight_sgd(d, xd, gd, wm, wbf, 0.05, scr, ws)
+        wap.wap_sgd_update(n_out * n_in, wm2, dW, 0.05, wbf2)
+        torch.cuda.synchronize()
+        same = torch.equal(wm, wm2) and torch.equal(wbf.view(torch.int16), wbf2.view(torch.int16))
+        if not (e[0] <= gu.TOL_BF16_OUT and e[1] <= gu.TOL_BF16_OUT and e[2] <= gu.TOL_F32_OUT and same):
+            bad.append(((B, n_in, n_out), [f"{v:.2e}" for v in e], same))
     assert not bad, bad
