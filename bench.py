@@ -100,6 +100,32 @@ def time_plain_steps(plan, buf, steps, warmup, torch):
     return (time.perf_counter() - t0) / steps
 
 
+def vendor_gemm_reference(torch):
+    """Context only (nothing of the product path runs through it): the rate of the vendor's bf16 GEMM (torch.matmul,
+    i.e. hipBLASLt / rocBLAS) on this machine, for a large square problem and for the plain GEMMs that have the shapes of
+    three VGG-16 layers at minibatch 64 (no im2col gather, operands already in matrix form).  It shows what this part
+    sustains under its own clock management, next to the datasheet peak the roofline fractions are quoted against."""
+    rows = []
+    for name, (M, N, K) in (("square", (8192, 8192, 8192)), ("conv3_2 as GEMM", (200704, 256, 2304)),
+                            ("conv4_2 as GEMM", (50176, 512, 4608)), ("conv5_2 as GEMM", (12544, 512, 4608))):
+        x = torch.randn(M, K, device="cuda", dtype=torch.bfloat16)
+        w = torch.randn(N, K, device="cuda", dtype=torch.bfloat16)
+        for _ in range(10):
+            y = x @ w.t()
+        torch.cuda.synchronize()
+        iters = 40
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            y = x @ w.t()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / iters
+        rows.append({"problem": name, "M": M, "N": N, "K": K, "us": round(dt * 1e6, 1),
+                     "tflops": round(2.0 * M * N * K / dt / 1e12, 1)})
+        del x, w, y
+    torch.cuda.empty_cache()
+    return {"library": "torch.matmul bf16 (hipBLASLt / rocBLAS)", "rows": rows}
+
+
 def cpu_baseline(net, image):
     """The fp64 oracle, as it stands, on a bounded sample of the headline workload (two images for VGG-16, sixteen
     for the AlexNet-style network): every conv and FC layer forward + data gradient + weight gradient (first layer's
@@ -447,6 +473,8 @@ def main():
             md.append(f"| {r['layer']} | {r['pass']} | {r['minibatch']} | {r['us']} | {r['tflops']} | "
                       f"{r['frac_peak']} | {r['gbs']} | {r['bound']} |")
 
+    if not a.no_table:
+        out["vendor_gemm_reference"] = vendor_gemm_reference(torch)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(net, image)
     if a.table_out and md:
