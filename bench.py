@@ -5,12 +5,17 @@ A "step" is one whole pass of the hot path over one synthetic minibatch: forward
 cross-entropy, backward (data and weight gradients of every conv / FC layer, ReLU and max-pool
 backward) and the SGD update, enqueued from the library's launch list on one stream.
 
-Prints ONE JSON line.  `value` is the step's algorithmic TFLOP/s (direct-convolution FLOP count,
-first layer's data gradient excluded) with all inputs resident in HBM.  `roofline` describes the
-kernel that takes the largest share of the step, timed with HIP events inside the timed region;
-`cpu_baseline` is the fp64 oracle on the host cores over a bounded sample of the same workload;
-`util_table` is the step-level utilisation-versus-per-GPU-minibatch sweep for both networks and
-`layers` the per-layer table of the headline workload (what a workload analysis unit would sum).
+Prints ONE short JSON line on stdout (its last line).  `value` is the step's algorithmic TFLOP/s
+(direct-convolution FLOP count, first layer's data gradient excluded) with all inputs resident in HBM.
+`roofline` describes the kernel that takes the largest share of the step, timed with HIP events inside
+the timed region; `cpu_baseline` is the fp64 oracle on the host cores over a bounded sample of the same
+workload; `util_table` is the step-level utilisation-versus-per-GPU-minibatch sweep for both networks
+(rows of [net, minibatch, ms per step, TFLOP/s, fraction of the bf16 peak]).
+
+Everything long goes to files, not to that line: `--detail-out` (JSON: per-kernel and per-operation
+breakdown of the step, the per-layer t_c tables of both networks from wap_profile_layer, the workload
+analysis decisions, the FC head as model-parallel slices, the vendor GEMM context) and `--table-out`
+(the same tables as Markdown).  Progress lines go to stderr.
 """
 from __future__ import annotations
 
@@ -30,6 +35,11 @@ import synth_inputs as si  # noqa: E402
 
 PEAK_BF16 = 2516.6  # TFLOP/s, dense bf16 MFMA
 PEAK_HBM = 8000.0   # GB/s
+BOUND_NAMES = ("mfma", "hbm", "launch/occupancy")
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
 def _arena(plan, torch):
@@ -205,7 +215,11 @@ def main():
     ap.add_argument("--link-gbs", type=float, default=76.8,
                     help="one-direction bandwidth of one xGMI link, GB/s (analytic t_s of the workload analysis)")
     ap.add_argument("--link-latency-us", type=float, default=10.0, help="latency of one ring step, microseconds")
-    ap.add_argument("--table-out", default=None, help="also write the tables as Markdown to this path")
+    ap.add_argument("--table-out", default=os.path.join(ROOT, "gpurun_out", "bench_tables.md"),
+                    help="the tables as Markdown go to this path")
+    ap.add_argument("--detail-out", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
+                    help="the full result (breakdowns and tables) as JSON goes to this path")
+    ap.add_argument("--profile-iters", type=int, default=20, help="timed samples per row of the per-layer tables")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs one replica on ONE GPU; --gpus above 1 is not supported "
@@ -326,7 +340,10 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{net} full training step (conv+FC fwd/bwd, ReLU, max-pool, softmax-CE, SGD "
                                f"lr={LR}), per-GPU minibatch {B}, 3x{image}x{image} input, 1000 classes",
-                   "net": net, "minibatch": B, "bias": bool(a.bias), "step_gflop": flops_step / 1e9, "ops_per_step": len(ops)},
+                   "net": net, "minibatch": B, "bias": bool(a.bias), "lr": LR,
+                   "lr_note": "config 5 names lr=0.01; 0.001 is used because 0.01 diverges on this recipe within three "
+                              "steps (work per step is identical)",
+                   "step_gflop": flops_step / 1e9, "ops_per_step": len(ops)},
         "frac_of_bf16_peak": value / PEAK_BF16,
         "images_per_s": B / (ms_per_step * 1e-3),
         "loss_after": loss,
@@ -384,12 +401,12 @@ def main():
             for (name, kind, nparam, desc) in descs:
                 nbytes = wap.wap_profile_scratch_bytes(kind, desc, mbs)
                 scratch = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
-                rows = wap.wap_profile_layer(kind, desc, mbs, 2, 7, scratch)
+                rows = wap.wap_profile_layer(kind, desc, mbs, 2, a.profile_iters, scratch)
                 for r in rows:
                     rows_out.append({"layer": name, "pass": ("fwd", "dgrad", "wgrad")[r.pass_], "minibatch": r.minibatch,
                                      "us": round(r.time_us_median, 2), "tflops": round(r.tflops, 2),
                                      "frac_peak": round(r.frac_of_bf16_peak, 4), "gbs": round(r.gbytes_per_s, 1),
-                                     "bound": ("mfma", "hbm")[r.bound], "params": nparam})
+                                     "bound": BOUND_NAMES[r.bound], "params": nparam})
                 del scratch
                 torch.cuda.empty_cache()
             return rows_out
@@ -397,8 +414,8 @@ def main():
         tables = {net: layer_table(net)}
         other = "alexnet" if net == "vgg16" else "vgg16"
         tables[other] = layer_table(other)
-        layers = [{k: v for k, v in r.items() if k != "params"} for r in tables[net]]
-        out["layers"] = layers
+        out["layers"] = {tn: [{k: v for k, v in r.items() if k != "params"} for r in rows] for tn, rows in tables.items()}
+        log("per-layer tables done")
 
         # ---- workload analysis (Eq. 1): t_c(l, d) from the table at per-GPU minibatch B/d (forward + both
         # backward passes; no data gradient for the first layer), t_s from the ring all-reduce model over one
@@ -446,41 +463,80 @@ def main():
                 n_sh = (n_out + d - 1) // d
                 desc = wap.fc_desc(1, n_in, n_sh, relu)
                 scratch = torch.empty(wap.wap_profile_scratch_bytes(1, desc, shard_mbs) + 256, dtype=torch.uint8, device="cuda")
-                for r in wap.wap_profile_layer(1, desc, shard_mbs, 2, 7, scratch):
+                for r in wap.wap_profile_layer(1, desc, shard_mbs, 2, a.profile_iters, scratch):
                     shard_rows.append({"layer": name, "d": d, "out_features": n_sh, "minibatch": r.minibatch,
                                        "pass": ("fwd", "dgrad", "wgrad")[r.pass_], "us": round(r.time_us_median, 2),
                                        "tflops": round(r.tflops, 2), "frac_peak": round(r.frac_of_bf16_peak, 4),
-                                       "gbs": round(r.gbytes_per_s, 1), "bound": ("mfma", "hbm")[r.bound]})
+                                       "gbs": round(r.gbytes_per_s, 1), "bound": BOUND_NAMES[r.bound]})
                 del scratch
                 torch.cuda.empty_cache()
         out["fc_shards"] = {"note": "FC layers of the headline network cut into d slices of output neurons, full minibatch per "
                                     "slice (model-parallel share of one GPU); dgrad is the slice's partial dx", "rows": shard_rows}
+        md.append(f"Utilisation versus per-GPU minibatch on one MI355X (bf16 MFMA, fp32 accumulation; fractions against "
+                  f"{PEAK_BF16} TFLOP/s and {PEAK_HBM / 1000:.0f} TB/s).  Written by `python bench.py` "
+                  f"(headline: {net}, minibatch {B}, {a.steps} timed steps; per-layer rows: wap_profile_layer, "
+                  f"{a.profile_iters} samples per row, median).\n\n## Whole training step\n")
         md.append("| net | minibatch | ms/step | TFLOP/s | frac of bf16 peak | images/s |\n|---|---|---|---|---|---|")
         for r in table:
             md.append(f"| {r['net']} | {r['minibatch']} | {r['ms_per_step']} | {r['tflops']} | "
                       f"{r['frac_of_bf16_peak']} | {r['images_per_s']} |")
-        md.append("\n| net | global minibatch | t_estimate ms by d | chosen d |\n|---|---|---|---|")
+        md.append("\n## Workload analysis (Eq. 1): measured t_c at minibatch B/d, analytic ring all-reduce t_s\n")
+        md.append("| net | global minibatch | t_estimate ms by d | chosen d |\n|---|---|---|---|")
         for r in wau_rows:
             md.append(f"| {r['net']} | {r['global_minibatch']} | "
                       + ", ".join(f"d={d}: {t}" for d, t in r["t_estimate_ms"].items()) + f" | {r['best_d']} |")
-        md.append("\n| FC layer | d | out features per shard | minibatch | pass | us | TFLOP/s | GB/s | side of ridge |\n"
+        md.append("\n## FC head as model-parallel slices (out_features / d per GPU, full minibatch)\n")
+        md.append("| FC layer | d | out features per shard | minibatch | pass | us | TFLOP/s | GB/s | bound |\n"
                   "|---|---|---|---|---|---|---|---|---|")
         for r in shard_rows:
             md.append(f"| {r['layer']} | {r['d']} | {r['out_features']} | {r['minibatch']} | {r['pass']} | {r['us']} | "
                       f"{r['tflops']} | {r['gbs']} | {r['bound']} |")
-        md.append("\n| layer | pass | minibatch | us | TFLOP/s | frac of peak | GB/s | side of ridge |\n|---|---|---|---|---|---|---|---|")
-        for r in layers:
-            md.append(f"| {r['layer']} | {r['pass']} | {r['minibatch']} | {r['us']} | {r['tflops']} | "
-                      f"{r['frac_peak']} | {r['gbs']} | {r['bound']} |")
+        for tn in ("vgg16", "alexnet"):
+            md.append(f"\n## Per-layer t_c(l, b), {tn}: one row per layer and pass, cells = us (fraction of the bf16 peak; "
+                      f"bound m = MFMA side, h = HBM side, L = launch / occupancy)\n")
+            md.append("| layer | pass | " + " | ".join(f"b={b}" for b in mbs) + " |\n|---|---|" + "---|" * len(mbs))
+            cell = {(r["layer"], r["pass"], r["minibatch"]): r for r in out["layers"][tn]}
+            seen = []
+            for r in out["layers"][tn]:
+                key = (r["layer"], r["pass"])
+                if key in seen:
+                    continue
+                seen.append(key)
+                cells = []
+                for b in mbs:
+                    c = cell[(r["layer"], r["pass"], b)]
+                    cells.append(f"{c['us']} ({c['frac_peak']:.3f} {'mhL'[BOUND_NAMES.index(c['bound'])]})")
+                md.append(f"| {r['layer']} | {r['pass']} | " + " | ".join(cells) + " |")
 
     if not a.no_table:
         out["vendor_gemm_reference"] = vendor_gemm_reference(torch)
     if not a.no_cpu_baseline:
+        log("timing the fp64 oracle on the host cores")
         out["cpu_baseline"] = cpu_baseline(net, image)
+    for path in (a.table_out, a.detail_out):
+        if path:
+            os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
     if a.table_out and md:
         with open(a.table_out, "w") as f:
             f.write("\n".join(md) + "\n")
-    print(json.dumps(out))
+    if a.detail_out:
+        with open(a.detail_out, "w") as f:
+            json.dump(out, f)
+    # the ONE line: the headline, its roofline and the CPU baseline; tables only in compact form
+    short_keys = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                  "vs_baseline", "dtype", "data", "config", "frac_of_bf16_peak", "images_per_s", "loss_after", "roofline",
+                  "cpu_baseline")
+    line = {k: out[k] for k in short_keys if k in out}
+    if "util_table" in out:
+        line["util_table"] = {"columns": ["net", "minibatch", "ms_per_step", "tflops", "frac_of_bf16_peak"],
+                              "rows": [[r["net"], r["minibatch"], r["ms_per_step"], r["tflops"], r["frac_of_bf16_peak"]]
+                                       for r in out["util_table"]]}
+    if "gradients_stored" in out:
+        line["gradients_stored_ms_per_step"] = round(out["gradients_stored"]["ms_per_step"], 4)
+    line["detail"] = {"json": os.path.relpath(a.detail_out, ROOT) if a.detail_out else None,
+                      "markdown": os.path.relpath(a.table_out, ROOT) if a.table_out and md else None}
+    sys.stderr.flush()
+    print(json.dumps(line), flush=True)
     return 0
 
 

@@ -28,6 +28,8 @@
  *     the text of the last failure on the calling thread.
  *   - `ws` is scratch the caller provides (device memory, 256-byte aligned); it holds split
  *     reduction partials and may be NULL when the query returns 0.
+ *   - Threads: calls may come from several host threads as long as each uses its own stream and
+ *     buffers; one-time kernel attribute set-up is guarded.  wap_last_error() is per thread.
  */
 #ifndef WAP_H
 #define WAP_H
@@ -71,16 +73,14 @@ typedef enum { WAP_PASS_FWD = 0, WAP_PASS_BWD_DATA = 1, WAP_PASS_BWD_WEIGHT = 2 
 int wap_version(void);
 const char* wap_last_error(void);
 
-/* Testing aid (process-wide, not thread safe): force the tile configuration of the forward-type
- * kernels (0..3), of the weight-gradient kernel (0..2) and the number of reduction splits; -1
- * restores the shape-driven choice.  Forced values that the shape cannot use are ignored, and the
- * *_workspace_bytes queries reflect the forced choice. */
-void wap_debug_force(int fwd_cfg, int wgrad_cfg, int nsplit);
-
 /* ---- convolution (primary node, Section 3.2.2; forward and backward halves of t_c, Eq. 1) ---- */
 
 /* Scratch bytes the given pass needs for this descriptor (0 is possible). */
 int wap_conv2d_workspace_bytes(const wap_conv_desc* d, int pass, size_t* bytes_out);
+
+/* The kernel instantiation the shape-driven dispatch launches for this descriptor and pass (the main kernel;
+ * host only, no device work).  The string is static. */
+int wap_conv2d_kernel_name(const wap_conv_desc* d, int pass, const char** name_out);
 
 /* y[n,p,q,k] = act( bias[k] + sum_{r,s,c} x[n, p*stride_h-pad_h+r, q*stride_w-pad_w+s, c] * w[k,r,s,c] ),
  * taps outside the image contribute zero.  x, w, y: bf16 device; bias: fp32 device [K] or NULL. */
@@ -178,7 +178,8 @@ int wap_maxpool_bwd(int32_t N, int32_t H, int32_t W, int32_t C, int32_t win, int
 /* Softmax cross-entropy, mean over the minibatch: p = softmax(z[b,:]) in fp32,
  * row_loss[b] = -log p[b,label_b] (fp32 [B]), loss = (1/B) sum_b row_loss[b] (one fp32 on device,
  * fixed summation order), dz[b,j] = (p[b,j] - [j == label_b]) / B stored bf16.
- * z bf16 [B][classes]; labels int32 [B], each in [0, classes) (not checked on the device). */
+ * z bf16 [B][classes]; labels int32 [B], each in [0, classes); a label outside that range gives its row
+ * no one-hot term and a row loss of 0 (never an out-of-range read). */
 int wap_softmax_xent_grad(int32_t B, int32_t classes, const void* z, const int32_t* labels,
                           float* loss, float* row_loss, void* dz, void* stream);
 
@@ -186,8 +187,8 @@ int wap_softmax_xent_grad(int32_t B, int32_t classes, const void* z, const int32
  * n elements; w_bf16 may be NULL. */
 int wap_sgd_update(int64_t n, float* w32, const float* dw, float lr, void* w_bf16, void* stream);
 
-/* Weight gradient and SGD update of one layer in one call (the weight-update tail of the backward time t_b,
- * Eq. 1): w32 <- w32 - lr * dw, w_bf16 <- bf16(w32), with dw exactly what wap_conv2d_bwd_weight / wap_fc_bwd
+/* Weight gradient and SGD update of one layer in one call (the weight-gradient half of t_c, Eq. 1,
+ * followed by the weight update of Section 3.2.3): w32 <- w32 - lr * dw, w_bf16 <- bf16(w32), with dw exactly what wap_conv2d_bwd_weight / wap_fc_bwd
  * compute, and the same fused multiply-add and rounding as wap_sgd_update: bit for bit the result of those
  * two calls.  w32: fp32 master weights, w_bf16: bf16 compute copy (both required, 16-byte aligned, layout of
  * the layer's weights).  Where the kernel that finishes the gradient applies the update itself (the matching
@@ -217,8 +218,11 @@ typedef struct {
     double frac_of_bf16_peak;  /* against 2516.6 TFLOP/s */
     double gbytes_per_s;       /* alg_bytes / median time */
     double frac_of_hbm_peak;   /* against 8000 GB/s */
-    int32_t bound;             /* 0 = MFMA side of the ridge, 1 = HBM side */
-    int32_t reserved;
+    int32_t bound;             /* 0 = MFMA side of the ridge, 1 = HBM side, 2 = launch / occupancy: the median
+                                  time is more than 4x the time of BOTH roofs (flops / 2516.6 TFLOP/s and
+                                  alg_bytes / 8 TB/s), i.e. too little work per launch to fill the chip -- the
+                                  small-minibatch under-utilisation of Section 2.2 */
+    int32_t reps_per_sample;   /* back-to-back launches one timed sample brackets (passes under 100 us: up to 8) */
 } wap_profile_row;
 
 /* Device scratch needed to profile the layer at every listed minibatch (inputs, outputs, workspace). */
@@ -227,8 +231,13 @@ int wap_profile_scratch_bytes(int kind /*0 conv, 1 fc*/, const void* desc, const
 
 /* Times fwd, bwd-data and bwd-weight of one layer at each minibatch in `minibatches`
  * (the descriptor's N / B is replaced by the minibatch) with HIP events on `stream`:
- * `warmup` untimed launches then `iters` timed ones per row.  Writes 3*n_mb rows (pass-major
- * within each minibatch).  Scratch contents are filled with a fixed pattern; this call
+ * `warmup` untimed launches (at least one), then `iters` timed samples per row, enqueued back to back
+ * with one event between consecutive samples and a single host synchronisation at the end, so that
+ * the host's launch latency is not inside a sample.  A sample is one pass (every kernel the pass
+ * launches: weight repacking, main kernel, split reduction), or several back-to-back passes when
+ * one is shorter than 100 us (reps_per_sample; times are per pass).  Writes 3*n_mb rows, ordered by
+ * minibatch and within a minibatch by pass (fwd, bwd-data, bwd-weight).  Operands are a fixed
+ * pseudo-random fill pattern generated on the device (times do not depend on values); this call
  * synchronises the stream. */
 int wap_profile_layer(int kind, const void* desc, const int32_t* minibatches, int32_t n_mb,
                       int32_t warmup, int32_t iters, void* scratch, size_t scratch_bytes,

@@ -53,7 +53,7 @@ class ProfileRow(ctypes.Structure):
                 ("alg_bytes", ctypes.c_double), ("time_us_median", ctypes.c_double),
                 ("time_us_min", ctypes.c_double), ("tflops", ctypes.c_double),
                 ("frac_of_bf16_peak", ctypes.c_double), ("gbytes_per_s", ctypes.c_double),
-                ("frac_of_hbm_peak", ctypes.c_double), ("bound", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("frac_of_hbm_peak", ctypes.c_double), ("bound", ctypes.c_int32), ("reps_per_sample", ctypes.c_int32)]
 
 
 _lib = None
@@ -118,6 +118,12 @@ def wap_conv2d_workspace_bytes(desc, pass_):
     out = ctypes.c_size_t(0)
     _check(lib().wap_conv2d_workspace_bytes(ctypes.byref(desc), int(pass_), ctypes.byref(out)))
     return out.value
+
+
+def wap_conv2d_kernel_name(desc, pass_):
+    out = ctypes.c_char_p()
+    _check(lib().wap_conv2d_kernel_name(ctypes.byref(desc), int(pass_), ctypes.byref(out)))
+    return out.value.decode()
 
 
 def wap_fc_workspace_bytes(desc, pass_):

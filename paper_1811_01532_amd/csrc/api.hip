@@ -165,6 +165,24 @@ int wap_conv2d_workspace_bytes(const wap_conv_desc* d, int pass, size_t* bytes_o
     return WAP_OK;
 }
 
+int wap_conv2d_kernel_name(const wap_conv_desc* d, int pass, const char** name_out) {
+    WAP_TRY(validate_conv(d));
+    if (!name_out) return set_error(WAP_EINVAL, "name_out is NULL");
+    if (pass == WAP_PASS_FWD) {
+        GemmGeom g = geom_conv_fwd(*d);
+        *name_out = fwd_like_kernel_name(g, false, plan_fwd_like(g, false));
+    } else if (pass == WAP_PASS_BWD_DATA) {
+        GemmGeom g = geom_conv_dgrad(*d);
+        *name_out = fwd_like_kernel_name(g, true, plan_fwd_like(g, true));
+    } else if (pass == WAP_PASS_BWD_WEIGHT) {
+        WgradGeom g = geom_conv_wgrad(*d);
+        *name_out = wgrad_kernel_name(g, plan_wgrad(g));
+    } else {
+        return set_error(WAP_EINVAL, "unknown pass %d", pass);
+    }
+    return WAP_OK;
+}
+
 int wap_conv2d_fwd(const wap_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
                    void* ws, size_t ws_bytes, void* stream) {
     WAP_TRY(validate_conv(d));

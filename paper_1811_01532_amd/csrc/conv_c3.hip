@@ -709,7 +709,7 @@ int launch_conv_c3_fwd(const GemmGeom& g, const bf16_t* x, const bf16_t* w, cons
         fa.dG8 = make_fastdiv((uint32_t)p.G8);
         fa.dKred = make_fastdiv((uint32_t)g.Kred);
         fa.dS3 = make_fastdiv((uint32_t)(g.S * 3));
-        static bool attr_done = false;
+        static std::atomic<bool> attr_done{false};
         if (!attr_done) {
             for (const void* f : {(const void*)conv_c3_fwd_strided_kernel<1>, (const void*)conv_c3_fwd_strided_kernel<2>}) {
                 hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
@@ -806,7 +806,7 @@ int launch_wgrad_c3(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_
         sa.dOH = make_fastdiv((uint32_t)g.P);
         sa.dSC4 = make_fastdiv((uint32_t)p.SC4);
         sa.dNVX = make_fastdiv((uint32_t)sa.nvx);
-        static bool attr_done = false;
+        static std::atomic<bool> attr_done{false};
         if (!attr_done) {
             for (const void* f : {(const void*)wgrad_c3_strided_kernel<1>, (const void*)wgrad_c3_strided_kernel<2>}) {
                 hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);

@@ -490,7 +490,7 @@ template <int FN, int TW, int FM, int PG, bool UP>
 int launch_tile2d_u(const TArgs& ta, hipStream_t st) {
     auto kfn = conv_tile2d_kernel<FN, TW, FM, PG, UP>;
     constexpr size_t smem = (size_t)(TW == 0 ? LDS_ROWS_FLAT : (TW == 28 ? LDS_ROWS_STRIP : MAX_PATCH)) * PITCH;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

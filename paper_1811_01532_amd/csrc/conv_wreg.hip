@@ -340,7 +340,14 @@ __global__ void pack_weights_multi_kernel(const PackJobs js, unsigned char* __re
 }  // namespace
 
 bool wreg_supported(const GemmGeom& g) {
-    return (g.IC % BK) == 0 && g.div_h == 1 && g.div_w == 1 && (g.Kred % 8) == 0;
+    // The kernel keeps a pixel's (row, column) base as two signed 16-bit halves of one register and addresses the
+    // activations with 32-bit byte offsets whose top value is the out-of-range sentinel: maps whose padded
+    // coordinates or byte size exceed those ranges go to the generic tiles.
+    const long h_hi = (long)(g.OH - 1) * g.mul_h - g.pad_h + g.R - 1, w_hi = (long)(g.OW - 1) * g.mul_w - g.pad_w + g.S - 1;
+    const bool coords_fit = h_hi < 32768 && w_hi < 32768 && g.pad_h < 32768 && g.pad_w < 32768;
+    const long imgs = (long)(g.M / ((long)g.OH * g.OW));
+    const bool bytes_fit = (double)imgs * g.IH * g.IW * g.IC * 2.0 <= (double)0xFFFFFF00u;
+    return (g.IC % BK) == 0 && g.div_h == 1 && g.div_w == 1 && (g.Kred % 8) == 0 && coords_fit && bytes_fit;
 }
 
 size_t wreg_smem_bytes() { return (size_t)NSTAGE * A_STAGE; }
@@ -395,7 +402,7 @@ int launch_wreg(const GemmGeom& g, int nsplit, const bf16_t* A, const bf16_t* Bw
     ka.out = out;
     ka.a_bytes = (unsigned)((size_t)(g.M / (g.OH * g.OW)) * g.IH * g.IW * g.IC * 2);
     ka.w_bytes = (unsigned)wreg_wt_bytes(g);
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_wreg_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)wreg_smem_bytes());

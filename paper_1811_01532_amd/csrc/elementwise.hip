@@ -345,12 +345,15 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const bf16_t* __restr
     __syncthreads();
     s = (red[0] + red[1]) + (red[2] + red[3]);
     const float inv = 1.f / s, invB = 1.f / (float)B;
+    // a label outside [0, classes) names no class: the row gets no one-hot term and contributes no loss (and no
+    // out-of-range read)
     const int lab = labels[b];
+    const bool lab_ok = (unsigned)lab < (unsigned)classes;
     for (int j = tid; j < classes; j += 256) {
         float p = expf(bf2f(zb[j]) - m) * inv;
         dz[(size_t)b * classes + j] = f2bf((p - (j == lab ? 1.f : 0.f)) * invB);
     }
-    if (tid == 0) row_loss[b] = -(bf2f(zb[lab]) - m - logf(s));
+    if (tid == 0) row_loss[b] = lab_ok ? -(bf2f(zb[lab]) - m - logf(s)) : 0.f;
 }
 
 // fixed-order mean of B row losses (single work-group tree)

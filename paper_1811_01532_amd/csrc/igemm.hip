@@ -377,7 +377,7 @@ size_t smem_bytes(const Cfg& c, bool b_tr) {
 template <int BM, int BN, int WMv, int WNv, bool B_TR, int MODE>
 int launch_one(const KArgs& ka, size_t smem, hipStream_t st) {
     auto kfn = igemm_kernel<BM, BN, WMv, WNv, B_TR, MODE>;
-    static bool attr_done = false;  // one attribute call per instantiation
+    static std::atomic<bool> attr_done{false};  // one attribute call per instantiation
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

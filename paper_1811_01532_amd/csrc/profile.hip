@@ -3,6 +3,7 @@
 // bf16 MFMA peak and GB/s against the HBM peak.  This is the input the workload analysis unit of
 // Section 3.2.1 needs to evaluate Eq. 1 for every candidate GPU count d (per-GPU minibatch B/d).
 #include <algorithm>
+#include <cmath>
 #include <vector>
 
 #include "wap_internal.h"
@@ -10,6 +11,9 @@
 using namespace wap;
 
 namespace {
+
+constexpr double kProfileSampleUs = 100.0;   // samples shorter than this bracket several launches
+constexpr double kLaunchBoundFactor = 4.0;   // slower than 4x both roofs: class 2 (launch / occupancy)
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -98,9 +102,17 @@ int wap_profile_layer(int kind, const void* desc, const int32_t* minibatches, in
     if (!scratch || (reinterpret_cast<uintptr_t>(scratch) & 255u))
         return set_error(WAP_EINVAL, "profile: scratch must be non-NULL and 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
-    hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
-        return set_error(WAP_EHIP, "profile: hipEventCreate failed");
+    // One event per sample boundary, all recorded without a host synchronisation in between: the queue never runs
+    // dry, so the host's launch latency is not part of a sample (a sample that starts on an idle queue is stamped
+    // before the host has finished enqueuing the pass).  Short passes are timed as `reps` back-to-back launches per
+    // sample, so that the few microseconds an event record costs between two kernels stay small against the sample.
+    std::vector<hipEvent_t> ev((size_t)iters + 1, nullptr);
+    for (auto& e : ev)
+        if (hipEventCreate(&e) != hipSuccess) {
+            for (auto& f : ev)
+                if (f) (void)hipEventDestroy(f);
+            return set_error(WAP_EHIP, "profile: hipEventCreate failed");
+        }
     int rc = WAP_OK;
     int nrows = 0;
     unsigned char* base = (unsigned char*)scratch;
@@ -137,17 +149,30 @@ int wap_profile_layer(int kind, const void* desc, const int32_t* minibatches, in
                 if (pass == 1) return launch_fwd_like(ps.gd, true, ps.pd, y, w, nullptr, false, dx, ws, st);
                 return launch_wgrad(ps.gw, ps.pw, x, y, dw, ws, st);
             };
-            for (int k = 0; k < warmup && rc == WAP_OK; ++k) rc = run();
+            // warm-up (at least one launch: its time sizes `reps`)
+            const int nwarm = warmup > 0 ? warmup : 1;
+            (void)hipEventRecord(ev[0], st);
+            for (int k = 0; k < nwarm && rc == WAP_OK; ++k) rc = run();
+            (void)hipEventRecord(ev[1], st);
+            if (rc != WAP_OK) break;
+            if (hipEventSynchronize(ev[1]) != hipSuccess) { rc = set_error(WAP_EHIP, "profile: event sync failed"); break; }
+            float wms = 0.f;
+            (void)hipEventElapsedTime(&wms, ev[0], ev[1]);
+            const double warm_us = (double)wms * 1000.0 / nwarm;
+            int reps = 1;
+            if (warm_us < kProfileSampleUs) reps = (int)std::min(8.0, std::ceil(kProfileSampleUs / std::max(warm_us, 1.0)));
+            (void)hipEventRecord(ev[0], st);
             for (int k = 0; k < iters && rc == WAP_OK; ++k) {
-                (void)hipEventRecord(e0, st);
-                rc = run();
-                (void)hipEventRecord(e1, st);
-                if (hipEventSynchronize(e1) != hipSuccess) rc = set_error(WAP_EHIP, "profile: event sync failed");
-                float ms = 0.f;
-                (void)hipEventElapsedTime(&ms, e0, e1);
-                t[k] = ms * 1000.f;
+                for (int q = 0; q < reps && rc == WAP_OK; ++q) rc = run();
+                (void)hipEventRecord(ev[(size_t)k + 1], st);
             }
             if (rc != WAP_OK) break;
+            if (hipEventSynchronize(ev[(size_t)iters]) != hipSuccess) { rc = set_error(WAP_EHIP, "profile: event sync failed"); break; }
+            for (int k = 0; k < iters; ++k) {
+                float ms = 0.f;
+                (void)hipEventElapsedTime(&ms, ev[(size_t)k], ev[(size_t)k + 1]);
+                t[k] = ms * 1000.f / (float)reps;
+            }
             std::vector<float> s(t);
             std::sort(s.begin(), s.end());
             wap_profile_row& r = rows_out[nrows++];
@@ -161,12 +186,18 @@ int wap_profile_layer(int kind, const void* desc, const int32_t* minibatches, in
             r.frac_of_bf16_peak = r.tflops / kPeakBf16Tflops;
             r.gbytes_per_s = r.alg_bytes / (r.time_us_median * 1e-6) / 1e9;
             r.frac_of_hbm_peak = r.gbytes_per_s / kPeakHbmGBs;
-            r.bound = (flops / r.alg_bytes >= kPeakBf16Tflops * 1e12 / (kPeakHbmGBs * 1e9)) ? 0 : 1;
-            r.reserved = 0;
+            // Which roof the pass sits under: the side of the ridge its arithmetic intensity falls on, unless the
+            // measured time is more than kLaunchBoundFactor times the time of BOTH roofs -- then neither the matrix
+            // pipes nor HBM explain it and the pass is bound by launch overhead / too few work-groups for the chip,
+            // the small-minibatch regime of Section 2.2.
+            const double t_mfma_us = flops / (kPeakBf16Tflops * 1e12) * 1e6;
+            const double t_hbm_us = r.alg_bytes / (kPeakHbmGBs * 1e9) * 1e6;
+            r.bound = (t_mfma_us >= t_hbm_us) ? 0 : 1;
+            if (r.time_us_median > kLaunchBoundFactor * std::max(t_mfma_us, t_hbm_us)) r.bound = 2;
+            r.reps_per_sample = reps;
         }
     }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
+    for (auto& e : ev) (void)hipEventDestroy(e);
     *rows_written = nrows;
     return rc;
 }

@@ -1,10 +1,13 @@
 // Internal declarations shared by the HIP translation units of libwap (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
 #include "../../include/wap.h"
+#include "../../include/wap_testing.h"
 
 namespace wap {
 

@@ -298,7 +298,7 @@ size_t smem_bytes(const Cfg& c) { return 2 * ((size_t)BK * (c.TC * 2 + 64) + (si
 template <int TC, int TK, int WCv, int WKv, int MODE>
 int launch_one(const WArgs& wa, size_t smem, hipStream_t st) {
     auto kfn = wgrad_kernel<TC, TK, WCv, WKv, MODE>;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

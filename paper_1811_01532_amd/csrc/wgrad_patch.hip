@@ -381,7 +381,7 @@ int launch_wgrad_patch(const WgradGeom& g, int nsplit, const bf16_t* x, const bf
     wa.dTx = make_fastdiv((uint32_t)wa.tiles_x);
     const size_t smem = 2 * (size_t)wa.buf_bytes;
     if (smem > LDS_BYTES) return set_error(WAP_EINVAL, "internal: patch weight-gradient tile does not fit LDS");
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         for (const void* f : {(const void*)wgrad_patch_kernel<1, false>, (const void*)wgrad_patch_kernel<2, false>,
                               (const void*)wgrad_patch_kernel<1, true>, (const void*)wgrad_patch_kernel<2, true>}) {

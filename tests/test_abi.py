@@ -21,9 +21,12 @@ def wap():
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "wap.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(wap_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("wap.h", "wap_testing.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(wap_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(wap):
@@ -193,3 +196,13 @@ def test_fused_update_entry_points_and_launch_list_order(wap):
         assert len(set(fused)) == len(fused) <= n_layers
         if len(fused) < n_layers or (flags & wap.WAP_STEP_BIAS):
             assert any(m == "sgd" for m in names)
+
+
+def test_wide_maps_leave_the_16bit_coordinate_kernel(wap):
+    """The weights-in-registers kernel keeps pixel coordinates in 16-bit halves: a map wider than that range must
+    be planned onto the generic tiles (host-side plan query, no device work)."""
+    wide = wap.conv_desc(2, 1, 40000, 64, 256, 1, 1, 1, 0)
+    assert wap.wap_conv2d_kernel_name(wide, wap.WAP_PASS_FWD).startswith("igemm_kernel")
+    narrow = wap.conv_desc(2, 100, 400, 64, 256, 1, 1, 1, 0)
+    assert wap.wap_conv2d_kernel_name(narrow, wap.WAP_PASS_FWD) == "conv_wreg_kernel"
+    assert wap.wap_conv2d_kernel_name(wap.conv_desc(64, 28, 28, 512, 512, 3, 3, 1, 1), wap.WAP_PASS_BWD_WEIGHT).startswith("wgrad_patch")

@@ -32,6 +32,8 @@ CASES = [
     # weights-in-registers kernel (ragged rows and columns, stride 2 forward, split reduction)
     ("wreg_forced_ragged", (2, 21, 23, 64, 200, 3, 3, 1, 1), (5, -1, -1)),
     ("wreg_forced_stride2_split2", (1, 30, 30, 128, 96, 3, 3, 2, 1), (5, -1, 2)),
+    # a map wider than the 16-bit pixel coordinates of the weights-in-registers kernel: planned onto the generic tiles
+    ("wide_map_1x1_w40000", (2, 1, 40000, 64, 256, 1, 1, 1, 0), (-1, -1, -1)),
     # patch-in-LDS kernel: chosen from the shape; ragged last tile, one and two channel slices, both widths
     ("patch_auto_k128_ragged", (2, 88, 88, 64, 128, 3, 3, 1, 1), (-1, -1, -1)),
     ("patch_auto_k256_two_slices", (1, 120, 121, 128, 256, 3, 3, 1, 1), (-1, -1, -1)),
