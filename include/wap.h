@@ -87,6 +87,21 @@ int wap_conv2d_kernel_name(const wap_conv_desc* d, int pass, const char** name_o
 int wap_conv2d_fwd(const wap_conv_desc* d, const void* x, const void* w, const float* bias,
                    void* y, void* ws, size_t ws_bytes, void* stream);
 
+/* wap_conv2d_fwd for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus `ws`: the packed-weight
+ * copy and split-reduction partials that wap_conv2d_fwd keeps in the caller's workspace live in a static device
+ * array of WAP_STATIC_SCRATCH_BYTES inside the library (every GPU the process uses holds its own copy until the
+ * process ends; its address is looked up once per device on the first call there, with that device current).
+ * Same kernels, bit-identical y.  No hipMalloc / hipFree / allocating library call, no synchronisation.
+ * WAP_EWORKSPACE (before any device work) when the layer's wap_conv2d_workspace_bytes(FWD) exceeds
+ * WAP_STATIC_SCRATCH_BYTES (every convolution of the two networks at minibatches 8..256 fits).
+ * All calls on one GPU share the one array and it keeps the last call's contents (each call overwrites what it
+ * reads, nothing needs clearing): calls that can overlap on one GPU -- different streams, or several host
+ * threads -- race on it; serialise them on one stream. */
+#define WAP_STATIC_SCRATCH_BYTES (16u << 20)
+int wap_conv2d_fwd_static_ws(const wap_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
+                             void* stream);
+
 /* Convolution forward followed by a 2x2 / stride-2 max-pool of its (bias / ReLU applied) output, the
  * conv -> ReLU -> pool chain of a VGG block (primary node plus its auxiliary nodes, Section 3.2.2):
  * y_pool[n,p/2,q/2,k] and argmax (uint8, r*2+s of the first maximum in window scan order) exactly as

@@ -137,6 +137,13 @@ def wap_conv2d_fwd(desc, x, w, bias, y, ws=None, stream=None):
                                 ctypes.c_size_t(_nbytes(ws)), _stream(stream)))
 
 
+WAP_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def wap_conv2d_fwd_static_ws(desc, x, w, bias, y, stream=None):
+    _check(lib().wap_conv2d_fwd_static_ws(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _stream(stream)))
+
+
 def wap_conv2d_fwd_pool2x2(desc, x, w, bias, y, y_pool, argmax, ws=None, stream=None):
     _check(lib().wap_conv2d_fwd_pool2x2(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _ptr(y_pool),
                                         _ptr(argmax), _ptr(ws), ctypes.c_size_t(_nbytes(ws)), _stream(stream)))

@@ -197,6 +197,55 @@ int wap_conv2d_fwd(const wap_conv_desc* d, const void* x, const void* w, const f
                            (bf16_t*)y, ws, (hipStream_t)stream);
 }
 
+// ---- forward convolution for callers that cannot allocate: the workspace is a static device array ----
+}  // extern "C" (reopened below: the array and its per-device address are file-scope objects)
+
+// One copy of this array exists on every GPU the library runs on, from module load until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress; kernels and launches get the per-device address.
+static __device__ __align__(256) unsigned char scratch[WAP_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_addr[kMaxDevices];
+
+// device address of `scratch` on the current device, looked up once per device (with that device current)
+int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return set_error(WAP_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return set_error(WAP_EUNSUPPORTED, "device ordinal %d above %d", dev, kMaxDevices - 1);
+    void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return set_error(WAP_EHIP, "hipGetSymbolAddress(static scratch): %s", hipGetErrorString(e));
+        g_scratch_addr[dev].store(p, std::memory_order_release);   // the same address whichever thread wins
+    }
+    *out = p;
+    return WAP_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int wap_conv2d_fwd_static_ws(const wap_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
+                             void* stream) {
+    WAP_TRY(validate_conv(d));
+    WAP_TRY(check_ptr(x, "x"));
+    WAP_TRY(check_ptr(w, "w"));
+    WAP_TRY(check_ptr(y, "y"));
+    if (bias && !aligned16(bias)) return set_error(WAP_EINVAL, "bias is not 16-byte aligned");
+    GemmGeom g = geom_conv_fwd(*d);
+    GemmPlan p = plan_fwd_like(g, false);
+    if (p.ws_bytes > (size_t)WAP_STATIC_SCRATCH_BYTES)
+        return set_error(WAP_EWORKSPACE, "conv2d_fwd_static_ws: this layer needs %zu bytes of workspace, the static scratch "
+                         "holds %zu; use wap_conv2d_fwd with a caller workspace", p.ws_bytes, (size_t)WAP_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if (p.ws_bytes) WAP_TRY(static_scratch(&ws));
+    return launch_fwd_like(g, false, p, (const bf16_t*)x, (const bf16_t*)w, bias, (d->flags & WAP_RELU) != 0,
+                           (bf16_t*)y, ws, (hipStream_t)stream);
+}
+
 int wap_conv2d_fwd_pool2x2_fused(const wap_conv_desc* d, int32_t* fused_out) {
     WAP_TRY(validate_conv(d));
     if (!fused_out) return set_error(WAP_EINVAL, "fwd_pool2x2_fused: NULL argument");

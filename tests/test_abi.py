@@ -206,3 +206,15 @@ def test_wide_maps_leave_the_16bit_coordinate_kernel(wap):
     narrow = wap.conv_desc(2, 100, 400, 64, 256, 1, 1, 1, 0)
     assert wap.wap_conv2d_kernel_name(narrow, wap.WAP_PASS_FWD) == "conv_wreg_kernel"
     assert wap.wap_conv2d_kernel_name(wap.conv_desc(64, 28, 28, 512, 512, 3, 3, 1, 1), wap.WAP_PASS_BWD_WEIGHT).startswith("wgrad_patch")
+
+
+def test_static_workspace_entry_point_rejects_oversized_layers_on_the_host(wap):
+    """The entry point that allocates nothing refuses, before any device work, a layer whose workspace exceeds its
+    static array (so the check runs without a GPU)."""
+    d = wap.conv_desc(64, 14, 14, 1024, 1024, 3, 3, 1, 1)
+    assert wap.wap_conv2d_workspace_bytes(d, wap.WAP_PASS_FWD) > wap.WAP_STATIC_SCRATCH_BYTES
+    with pytest.raises(wap.WapError) as ei:
+        wap.wap_conv2d_fwd_static_ws(d, 4096, 8192, None, 12288, stream=0)
+    assert ei.value.status == wap.WAP_EWORKSPACE
+    text = open(os.path.join(ROOT, "include", "wap.h")).read()
+    assert re.search(r"#define\s+WAP_STATIC_SCRATCH_BYTES\s+\(16u\s*<<\s*20\)", text)
