@@ -178,7 +178,15 @@ const char* patch_kernel_name(const GemmGeom& g);
 int launch_patch(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
                  hipStream_t st, const bf16_t* mask = nullptr);
 
-// stride-1 convolution on 8 x 32-pixel 2-D tiles for 64 / 128 output channels (conv_tile2d.hip)
+// stride-1 convolution on 256-pixel 2-D tiles x 64 output channels, three work-groups per CU (conv_tile64.hip)
+int tile64_width(const GemmGeom& g);  // 0: not applicable
+const char* tile64_kernel_name(const GemmGeom& g, bool unpool);
+bool tile64_fuses_unpool(const GemmGeom& g);
+int launch_tile64(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
+                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am);
+
+// stride-1 convolution with double-buffered 32-channel patch slices: 2-D, strip and flat tiles (conv_tile2d.hip;
+// it hands the shapes of conv_tile64.hip on to that kernel)
 int tile2d_supported(const GemmGeom& g);
 bool tile2d_preferred(const GemmGeom& g);
 const char* tile2d_kernel_name(const GemmGeom& g, bool unpool);
