@@ -407,6 +407,12 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
         p.ws_bytes = 0;
         return p;
     }
+    if (b_tr && (g_force_fwd_cfg < 0 || g_force_fwd_cfg == 9) && dgrad_thin_supported(g)) {
+        p.cfg = 9;  // at most four output columns (gradient w.r.t. a 3-channel image): vector-ALU kernel
+        p.nsplit = 1;
+        p.ws_bytes = dgrad_thin_ws_bytes(g);
+        return p;
+    }
     int mode = classify_mode(g, b_tr);
     int ktiles = (g.Kred + BK - 1) / BK;
     auto tiles = [&](int c) {
@@ -468,6 +474,7 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
         return launch_relu_bwd(out, relu_mask, out, (size_t)g.M * g.Ncols, st);
     }
     if (plan.cfg == 8) return launch_conv_c3_fwd(g, A, Bw, bias, relu, out, st);
+    if (plan.cfg == 9) return launch_dgrad_thin(g, A, Bw, out, ws, st);
     KArgs ka;
     ka.A = A;
     ka.Bw = Bw;
@@ -564,6 +571,7 @@ const char* fwd_like_kernel_name(const GemmGeom& g, bool b_tr, const GemmPlan& p
     if (plan.cfg == 6) return patch_kernel_name(g);
     if (plan.cfg == 7) return tile2d_kernel_name(g, unpool);
     if (plan.cfg == 8) return conv_c3_fwd_kernel_name(g);
+    if (plan.cfg == 9) return "dgrad_thin_kernel";
     static const char* names[5][2][3] = {
         {{"igemm_kernel<256,256,2,4,false,0>", "", ""}, {"igemm_kernel<256,256,2,4,true,0>", "", ""}},
         {{"igemm_kernel<128,128,2,2,false,0>", "igemm_kernel<128,128,2,2,false,1>", "igemm_kernel<128,128,2,2,false,2>"},

@@ -152,6 +152,11 @@ const char* wgrad_c3_kernel_name(const WgradGeom& g);
 int wgrad_c3_nsplit(const WgradGeom& g);
 int launch_wgrad_c3(const WgradGeom& g, int nsplit, const bf16_t* x, const bf16_t* dy, float* part, hipStream_t st);
 
+// data gradient with at most four output columns, on the vector ALUs (dgrad_thin.hip); g = data-gradient geometry
+bool dgrad_thin_supported(const GemmGeom& g);
+size_t dgrad_thin_ws_bytes(const GemmGeom& g);
+int launch_dgrad_thin(const GemmGeom& g, const bf16_t* dy, const bf16_t* w, bf16_t* dx, void* ws, hipStream_t st);
+
 // weights-in-registers large-tile kernel (conv_wreg.hip)
 bool wreg_supported(const GemmGeom& g);
 inline size_t wreg_wt_bytes(const GemmGeom& g) { return (size_t)((g.Ncols + 31) / 32) * 32 * g.Kred * 2; }  // packed copy
