@@ -17,12 +17,22 @@ pytestmark = pytest.mark.gpu
 LAYERS = [
     ("vgg_conv1_1_b64", 64, 224, 3, 64, 3, 1, 1),
     ("vgg_conv1_2_b64", 64, 224, 64, 64, 3, 1, 1),
+    ("vgg_conv2_1_b64", 64, 112, 64, 128, 3, 1, 1),     # 128-channel 2-D tiles forward, 64-channel tiles backward
+    ("vgg_conv3_1_b64", 64, 56, 128, 256, 3, 1, 1),
     ("vgg_conv3_2_b64", 64, 56, 256, 256, 3, 1, 1),
+    ("vgg_conv4_1_b64", 64, 28, 256, 512, 3, 1, 1),
     ("vgg_conv4_2_b64", 64, 28, 512, 512, 3, 1, 1),
     ("vgg_conv5_1_b64", 64, 14, 512, 512, 3, 1, 1),
     ("alex_conv1_b32", 32, 224, 3, 64, 11, 4, 2),
     ("alex_conv2_b32", 32, 27, 64, 192, 5, 1, 2),
     ("alex_conv3_b32", 32, 13, 192, 384, 3, 1, 1),
+    ("alex_conv4_b32", 32, 13, 384, 256, 3, 1, 1),
+    ("alex_conv5_b32", 32, 13, 256, 256, 3, 1, 1),
+    # small minibatches: the tile rules differ there (thin flat tiles, split reductions of the generic kernel)
+    ("vgg_conv4_2_b8", 8, 28, 512, 512, 3, 1, 1),
+    ("vgg_conv4_2_b16", 16, 28, 512, 512, 3, 1, 1),
+    ("vgg_conv5_1_b8", 8, 14, 512, 512, 3, 1, 1),
+    ("vgg_conv5_1_b16", 16, 14, 512, 512, 3, 1, 1),
 ]
 
 
@@ -217,3 +227,45 @@ def test_pooled_layer_fused_paths_full_size(orc, name, N, H, C, K):
     ref = orc.conv2d_bwd_weight_at(x64, routed, (K, 3, 3, C), iw, (1, 1), (1, 1))
     e = gu.rel_err(dwh[iw], ref)
     assert e <= gu.TOL and e <= gu.TOL_F32_OUT, f"{name} unpool+wgrad sampled rel err {e}"
+
+
+def test_vgg_conv5_3_with_its_separate_pool_backward_full_size(orc):
+    """The last pooled VGG-16 layer keeps separate pooling kernels (its 14 x 14 map gives weight-gradient tiles that
+    pooling windows would straddle): conv5_3 forward, 2x2 pool, pool backward with the ReLU mask, data gradient, at
+    minibatch 64.  The pooling passes are compared with the oracle on the whole tensor, bit for bit (teacher forced on
+    the device's own convolution output); the convolutions on sampled coordinates."""
+    import paper_1811_01532_amd as wap
+    N, H, C, K = 64, 14, 512, 512
+    print("[case] full-size vgg conv5_3 + separate pool backward", flush=True)
+    xb = np.maximum(si.normal_bf16(si.rng(950, 0), (N, H, H, C)).view(np.int16), 0).view(np.uint16)  # a ReLU output
+    wb = si.he_weight_bf16(si.rng(950, 1), (K, 3, 3, C))
+    gpb = si.normal_bf16(si.rng(950, 2), (N, H // 2, H // 2, K))
+    xd, wd, gpd = gu.dev_bf16(xb), gu.dev_bf16(wb), gu.dev_bf16(gpb)
+    d = wap.conv_desc(N, H, H, C, K, 3, 3, 1, 1, relu=True)
+    ws = gu.workspace(max(wap.wap_conv2d_workspace_bytes(d, p) for p in (0, 1, 2)))
+    y = torch.empty((N, H, H, K), dtype=torch.bfloat16, device="cuda")
+    yp = torch.empty((N, H // 2, H // 2, K), dtype=torch.bfloat16, device="cuda")
+    am = torch.empty((N, H // 2, H // 2, K), dtype=torch.uint8, device="cuda")
+    dy = torch.empty((N, H, H, K), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((N, H, H, C), dtype=torch.bfloat16, device="cuda")
+    wap.wap_conv2d_fwd(d, xd, wd, None, y, ws)
+    wap.wap_maxpool_fwd(N, H, H, K, 2, 2, y, yp, am)
+    wap.wap_maxpool_bwd(N, H, H, K, 2, 2, gpd, am, yp, dy)          # ReLU derivative fused: windows with y <= 0 dropped
+    wap.wap_conv2d_bwd_data_relu(d, dy, wd, xd, dx, ws)
+    torch.cuda.synchronize()
+    y64 = gu.host_f64(y)
+    ref_p, ref_am = orc.maxpool_fwd(y64, 2, 2)
+    assert np.array_equal(gu.host_f64(yp), ref_p) and np.array_equal(am.cpu().numpy(), ref_am)
+    g64 = orc.bf16_bits_to_f64(gpb)
+    routed = orc.maxpool_bwd(np.where(ref_p > 0.0, g64, 0.0), ref_am, (N, H, H, K), 2, 2)
+    assert np.array_equal(gu.host_f64(dy), routed)
+    x64, w64 = orc.bf16_bits_to_f64(xb), orc.bf16_bits_to_f64(wb)
+    rng = np.random.default_rng(951)
+    iy = _border_indices((N, H, H, K), rng, 4096)
+    e = gu.rel_err(y64.ravel()[iy], orc.conv2d_fwd_at(x64, w64, iy, (1, 1), (1, 1), relu=True))
+    assert e <= gu.TOL and e <= gu.TOL_BF16_OUT, f"conv5_3 fwd sampled rel err {e}"
+    ix = _border_indices((N, H, H, C), rng, 4096)
+    ref = orc.conv2d_bwd_data_at(routed, w64, (N, H, H, C), ix, (1, 1), (1, 1))
+    ref = np.where(x64.ravel()[ix] > 0.0, ref, 0.0)
+    e = gu.rel_err(gu.host_f64(dx).ravel()[ix], ref)
+    assert e <= gu.TOL and e <= gu.TOL_BF16_OUT, f"conv5_3 dgrad sampled rel err {e}"
