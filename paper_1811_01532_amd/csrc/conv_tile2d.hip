@@ -47,6 +47,7 @@ struct TArgs {
     bf16_t* out;         // may be NULL when only the pooled output is wanted
     bf16_t* pool_y;      // optional: 2x2 / stride-2 max-pool of the output tile ...
     uint8_t* pool_am;    // ... and the position r*2+s of the first maximum of every window
+    float* colsum;       // optional: [tiles_m][Ncols] column sums of this tile's stored (masked) rows, for a bias gradient
     GemmGeom g;
     int tiles_x, tiles_y, tiles_img, tiles_m, tiles_n;
     int RWB, buf_bytes;  // LDS byte stride of a patch row, bytes of one patch buffer
@@ -478,6 +479,7 @@ __global__ __launch_bounds__(NT, 2) void conv_tile2d_kernel(const TArgs a) {
             }
     }
     __syncthreads();
+    float csum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // column sums over this thread's rows (its 8 channels)
     for (int row = tid / VPR; row < BM; row += RPP) {
         const int idx = row;
         const int m = FLAT ? m0 + idx : (img * g.OH + oh0 + idx / TWD) * g.OW + ow0 + idx % TWD;
@@ -486,6 +488,28 @@ __global__ __launch_bounds__(NT, 2) void conv_tile2d_kernel(const TArgs a) {
         const size_t o = (size_t)m * g.Ncols + n0 + (tid % VPR) * 8;
         if (a.mask) vv = relu_mask8(vv, *reinterpret_cast<const u32x4*>(a.mask + o));
         if (a.out) *reinterpret_cast<u32x4*>(a.out + o) = vv;
+        if (a.colsum) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                csum[2 * k] += __uint_as_float(vv[k] << 16);
+                csum[2 * k + 1] += __uint_as_float(vv[k] & 0xffff0000u);
+            }
+        }
+    }
+    // ---- column sums of the stored tile (the bias gradient of the layer whose pre-activation gradient this is): the
+    // RPP row groups are added in group order through LDS, one partial row per pixel tile; a second kernel adds the
+    // tiles in a fixed order ----
+    if (a.colsum) {
+        __syncthreads();  // the staged tile has been read
+        float* red = reinterpret_cast<float*>(smem);  // [RPP][BN]
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[(tid / VPR) * BN + (tid % VPR) * 8 + e] = csum[e];
+        __syncthreads();
+        if (tid < BN) {
+            float t = red[tid];
+            for (int k = 1; k < RPP; ++k) t += red[k * BN + tid];
+            a.colsum[(size_t)tm * g.Ncols + n0 + tid] = t;
+        }
     }
     // ---- fused 2x2 / stride-2 max-pool of the staged (bias / ReLU applied, bf16) tile: tile origin and size are
     // even and the whole tile is staged, so every window is complete.  A flat tile is a whole number of row pairs
@@ -744,6 +768,14 @@ bool tile2d_fuses_unpool(const GemmGeom& g) {
     return ((c.th + g.R - 1) / 2 + 1) * ((c.tw + g.S - 1) / 2 + 1) <= 2 * (NT / 4);  // windows per patch: 2 per 4 threads
 }
 
+// partial rows (pixel tiles) the epilogue's column sums come in: [tile2d_colsum_rows][Ncols]
+int tile2d_colsum_rows(const GemmGeom& g) {
+    if (const int tw = tile64_width(g)) return (g.M / (g.OH * g.OW)) * (g.OW / tw) * (g.OH / (256 / tw));
+    const TileCfg c = tile_cfg(g);
+    if (c.variant >= 2) return (g.M + (c.variant == 3 ? 192 : 224) - 1) / (c.variant == 3 ? 192 : 224);
+    return (g.M / (g.OH * g.OW)) * (g.OW / c.tw) * (g.OH / c.th);
+}
+
 // can the epilogue also emit the 2x2 / stride-2 max-pool of the output?
 bool tile2d_fuses_pool(const GemmGeom& g) {
     if (!tile2d_supported(g)) return false;
@@ -755,9 +787,12 @@ bool tile2d_fuses_pool(const GemmGeom& g) {
 }
 
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am) {
-    if (tile64_width(g)) return launch_tile64(g, A, Wp, bias, relu, out, st, mask, pool_y, pool_am, unpool_am);
+                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am,
+                  float* colsum) {
+    if (colsum && pool_y) return set_error(WAP_EINVAL, "internal: column sums and the fused pool share the staging area");
+    if (tile64_width(g)) return launch_tile64(g, A, Wp, bias, relu, out, st, mask, pool_y, pool_am, unpool_am, colsum);
     TArgs ta = {};
+    ta.colsum = colsum;
     ta.mask = mask;
     if (unpool_am && !tile2d_fuses_unpool(g))
         return set_error(WAP_EINVAL, "internal: fused max-pool backward not available for this shape");

@@ -37,6 +37,7 @@ struct T64Args {
     bf16_t* out;           // may be NULL when only the pooled output is wanted
     bf16_t* pool_y;        // optional: 2x2 / stride-2 max-pool of the output tile ...
     uint8_t* pool_am;      // ... and the position r*2+s of the first maximum of every window
+    float* colsum;         // optional: [tiles_m][64] column sums of this tile's stored (masked) rows, for a bias gradient
     GemmGeom g;
     int tiles_x, tiles_img, tiles_m;
     int RW, patch_len;     // patch row width in pixels (tile width + S - 1), patch pixels to load
@@ -290,12 +291,35 @@ __global__ __launch_bounds__(NT, 3) void conv_tile64_kernel(const T64Args a) {
         }
     }
     __syncthreads();
+    float csum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // column sums over this thread's rows (its 8 channels)
     for (int row = tid / VPR; row < BM; row += RPP) {
         const int m = (img * g.OH + oh0 + row / TW) * g.OW + ow0 + row % TW;
         u32x4 vv = *reinterpret_cast<const u32x4*>(smem + row * OPITCH + (tid % VPR) * 16);
         const size_t o = (size_t)m * BN + (tid % VPR) * 8;
         if (a.mask) vv = relu_mask8(vv, *reinterpret_cast<const u32x4*>(a.mask + o));
         if (a.out) *reinterpret_cast<u32x4*>(a.out + o) = vv;
+        if (a.colsum) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                csum[2 * k] += __uint_as_float(vv[k] << 16);
+                csum[2 * k + 1] += __uint_as_float(vv[k] & 0xffff0000u);
+            }
+        }
+    }
+    // ---- column sums of the stored tile (the bias gradient of the layer whose pre-activation gradient this is): the
+    // RPP row groups are added in group order through LDS, one partial row per pixel tile; a second kernel adds the
+    // tiles in a fixed order ----
+    if (a.colsum) {
+        __syncthreads();  // the staged tile has been read
+        float* red = reinterpret_cast<float*>(smem);  // [RPP][BN]
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[(tid / VPR) * BN + (tid % VPR) * 8 + e] = csum[e];
+        __syncthreads();
+        if (tid < BN) {
+            float t = red[tid];
+            for (int k = 1; k < RPP; ++k) t += red[k * BN + tid];
+            a.colsum[(size_t)tm * BN + tid] = t;
+        }
     }
     // ---- fused 2x2 / stride-2 max-pool of the staged (bias / ReLU applied, bf16) tile: tile origin and size are
     // even, so every window is complete.  Same rule as maxpool_fwd_kernel: first maximum in (r, s) order. ----
@@ -378,7 +402,8 @@ bool tile64_fuses_unpool(const GemmGeom& g) {
 }
 
 int launch_tile64(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am) {
+                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am,
+                  float* colsum) {
     const int tw = tile64_width(g);
     if (!tw) return set_error(WAP_EINVAL, "internal: 64-channel tile kernel not applicable");
     if (unpool_am && !tile64_fuses_unpool(g))
@@ -395,6 +420,7 @@ int launch_tile64(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
     ta.out = out;
     ta.pool_y = pool_y;
     ta.pool_am = pool_am;
+    ta.colsum = colsum;
     ta.g = g;
     ta.tiles_x = g.OW / tw;
     ta.tiles_img = ta.tiles_x * (g.OH / th);

@@ -454,6 +454,89 @@ int launch_fill_bf16(bf16_t* p, size_t n, uint32_t seed, hipStream_t st) {
     return check_launch("fill");
 }
 
+// ---- fixed-order column sums of fp32 matrices [rows][cols], cols % 4 == 0 (the per-tile partial sums the convolution
+// epilogues leave for the bias gradients), every matrix of a step in one launch.  First stage: a work-group adds one
+// chunk of rows of one matrix, thread (row sub-index, 16-byte column vector) every RP-th row, then the RP partial sums
+// in order.  Second stage: a thread adds the chunks of one column vector in order. ----
+__global__ __launch_bounds__(256) void colsum_f32_multi_kernel(const ColsumJobs js, unsigned char* __restrict__ base) {
+    __shared__ float4 red[256];
+    int j = 0;
+    while (j + 1 < js.n && (int)blockIdx.x >= js.first[j + 1]) ++j;
+    const ColsumJob& jb = js.job[j];
+    const int local = (int)blockIdx.x - js.first[j];
+    const int cv = jb.cols / 4;
+    const int vpb = cv < 256 ? cv : 256;
+    const int colblocks = (cv + vpb - 1) / vpb;
+    const int chunk = local / colblocks, cb = local - chunk * colblocks;
+    const int rp = 256 / vpb;
+    const int vec = threadIdx.x % vpb, rsub = threadIdx.x / vpb;
+    const int v = cb * vpb + vec;
+    const float* part = reinterpret_cast<const float*>(base + jb.part_off);
+    float* part2 = reinterpret_cast<float*>(base + jb.part2_off);
+    const int rpc = (jb.rows + jb.chunks - 1) / jb.chunks;
+    const int r0 = chunk * rpc;
+    const int r1 = r0 + rpc < jb.rows ? r0 + rpc : jb.rows;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (rsub < rp && v < cv)
+        for (int r = r0 + rsub; r < r1; r += rp) {
+            const float4 t = *reinterpret_cast<const float4*>(part + (size_t)r * jb.cols + (size_t)v * 4);
+            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (rsub == 0 && v < cv) {
+        for (int k = 1; k < rp; ++k) {
+            const float4 t = red[k * vpb + vec];
+            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+        *reinterpret_cast<float4*>(part2 + (size_t)chunk * jb.cols + (size_t)v * 4) = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void colsum_f32_finish_kernel(const ColsumJobs js, unsigned char* __restrict__ base) {
+    const int t = blockIdx.x * 256 + threadIdx.x;  // column vector in the concatenation of all matrices
+    int j = 0, v0 = 0;
+    while (j < js.n && t >= v0 + js.job[j].cols / 4) { v0 += js.job[j].cols / 4; ++j; }
+    if (j >= js.n) return;
+    const ColsumJob& jb = js.job[j];
+    const int v = t - v0;
+    const float* part2 = reinterpret_cast<const float*>(base + jb.part2_off);
+    float4 s = *reinterpret_cast<const float4*>(part2 + (size_t)v * 4);
+    for (int k = 1; k < jb.chunks; ++k) {
+        const float4 u = *reinterpret_cast<const float4*>(part2 + (size_t)k * jb.cols + (size_t)v * 4);
+        s.x += u.x; s.y += u.y; s.z += u.z; s.w += u.w;
+    }
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(base + jb.out_off) + (size_t)v * 4) = s;
+}
+
+int colsum_f32_chunks(size_t rows) {
+    size_t chunks = (rows + 63) / 64;
+    if (chunks > 64) chunks = 64;
+    return (int)(chunks < 1 ? 1 : chunks);
+}
+
+int colsum_jobs_add(ColsumJobs& js, int rows, int cols, size_t part_off, size_t part2_off, size_t out_off) {
+    if (js.n >= kMaxColsumJobs || (cols & 3) != 0 || rows < 1) return -1;
+    ColsumJob& jb = js.job[js.n];
+    jb.rows = rows; jb.cols = cols; jb.chunks = colsum_f32_chunks((size_t)rows);
+    jb.part_off = part_off; jb.part2_off = part2_off; jb.out_off = out_off;
+    const int cv = cols / 4, vpb = cv < 256 ? cv : 256;
+    if (js.n == 0) js.first[0] = 0;
+    js.first[js.n + 1] = js.first[js.n] + jb.chunks * ((cv + vpb - 1) / vpb);
+    return js.n++;
+}
+
+int launch_colsum_f32_multi(const ColsumJobs& js, void* base, hipStream_t st) {
+    if (js.n < 1) return WAP_OK;
+    hipLaunchKernelGGL(colsum_f32_multi_kernel, dim3(js.first[js.n]), dim3(256), 0, st, js, (unsigned char*)base);
+    int rc = check_launch("colsum_f32_multi");
+    if (rc != WAP_OK) return rc;
+    int vecs = 0;
+    for (int j = 0; j < js.n; ++j) vecs += js.job[j].cols / 4;
+    hipLaunchKernelGGL(colsum_f32_finish_kernel, dim3((vecs + 255) / 256), dim3(256), 0, st, js, (unsigned char*)base);
+    return check_launch("colsum_f32_finish");
+}
+
 // Row chunks of the first stage: about 32 loads per thread (a work-group covers min(vectors per row, 256) vectors side
 // by side and 256 / that many rows per pass), at most ~8 work-groups per CU over all column blocks.
 int bias_grad_chunks(size_t rows, int cols) {
@@ -462,6 +545,7 @@ int bias_grad_chunks(size_t rows, int cols) {
     const int vpb = cv < 256 ? cv : 256;
     const int rp = 256 / vpb;
     const int colblocks = (cv + vpb - 1) / vpb;
+    if (rows <= 512) return 1;  // a minibatch of rows (FC layers): one chunk, its sums are the result (no second launch)
     size_t chunks = (rows + (size_t)32 * rp - 1) / ((size_t)32 * rp);
     size_t cap = (size_t)kNumCU * 8 / colblocks;
     if (cap < 1) cap = 1;
@@ -475,12 +559,13 @@ int launch_bias_grad(size_t rows, int cols, const bf16_t* dy, float* db, float* 
     const int vecw = (cols & 7) == 0 ? 8 : 1;
     const int cv = (cols + vecw - 1) / vecw;
     const int colblocks = (cv + 255) / 256;  // the kernel covers min(cv, 256) vectors per work-group
+    float* dst = chunks == 1 ? db : part;  // a single chunk writes the result itself
     if (vecw == 8)
-        hipLaunchKernelGGL(bias_grad_kernel<8>, dim3(chunks, colblocks), dim3(256), 0, st, dy, part, rows, cols, rpc);
+        hipLaunchKernelGGL(bias_grad_kernel<8>, dim3(chunks, colblocks), dim3(256), 0, st, dy, dst, rows, cols, rpc);
     else
-        hipLaunchKernelGGL(bias_grad_kernel<1>, dim3(chunks, colblocks), dim3(256), 0, st, dy, part, rows, cols, rpc);
+        hipLaunchKernelGGL(bias_grad_kernel<1>, dim3(chunks, colblocks), dim3(256), 0, st, dy, dst, rows, cols, rpc);
     int rc = check_launch("bias_grad");
-    if (rc != WAP_OK) return rc;
+    if (rc != WAP_OK || chunks == 1) return rc;
     return launch_reduce_f32(part, chunks, (size_t)cols, db, st);
 }
 

@@ -462,7 +462,9 @@ GemmPlan plan_fwd_like(const GemmGeom& g, bool b_tr) {
 int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf16_t* A,
                     const bf16_t* Bw, const float* bias, bool relu, bf16_t* out, void* ws,
                     hipStream_t st, hipEvent_t ev_mid, const bf16_t* relu_mask, hipEvent_t ev_packed,
-                    const void* prepacked, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am) {
+                    const void* prepacked, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am, float* colsum) {
+    if (colsum && (fwd_like_colsum_rows(g, plan) == 0 || pool_y))
+        return set_error(WAP_EINVAL, "internal: fused column sums not available for this plan");
     if ((pool_y || pool_am) && !(pool_y && pool_am && fwd_like_fuses_pool(g, plan)))
         return set_error(WAP_EINVAL, "internal: fused pooling not available for this plan");
     if (unpool_am && !fwd_like_fuses_unpool(g, plan))
@@ -498,7 +500,7 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
         }
         if (ev_packed) (void)hipEventRecord(ev_packed, st);
         return plan.cfg == 6 ? launch_patch(g, A, wp, bias, relu, out, st, relu_mask)
-                             : launch_tile2d(g, A, wp, bias, relu, out, st, relu_mask, pool_y, pool_am, unpool_am);
+                             : launch_tile2d(g, A, wp, bias, relu, out, st, relu_mask, pool_y, pool_am, unpool_am, colsum);
     }
     if (plan.cfg == 5) {
         // the (small) weight tensor is first repacked into MFMA fragment order (taps flipped and
@@ -562,6 +564,9 @@ bool fwd_like_fuses_pool(const GemmGeom& g, const GemmPlan& plan) {
     return plan.cfg == 7 && (g.OH % 2) == 0 && (g.OW % 2) == 0 && tile2d_fuses_pool(g);
 }
 bool fwd_like_fuses_unpool(const GemmGeom& g, const GemmPlan& plan) { return plan.cfg == 7 && tile2d_fuses_unpool(g); }
+int fwd_like_colsum_rows(const GemmGeom& g, const GemmPlan& plan) {
+    return plan.cfg == 7 && (g.Ncols % 8) == 0 ? tile2d_colsum_rows(g) : 0;
+}
 bool fwd_like_fuses_mask(const GemmGeom& g, const GemmPlan& plan) {
     return (plan.cfg == 6 || plan.cfg == 7) && (g.Ncols % 8) == 0;
 }

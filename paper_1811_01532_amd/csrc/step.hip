@@ -17,7 +17,7 @@ namespace {
 
 enum OpKind {
     OP_PACK, OP_CONV_FWD, OP_POOL_FWD, OP_FC_FWD, OP_SOFTMAX, OP_RELU_BWD, OP_POOL_BWD,
-    OP_FC_DX, OP_FC_DW, OP_CONV_WGRAD, OP_CONV_DGRAD, OP_SGD, OP_BIAS_GRAD
+    OP_FC_DX, OP_FC_DW, OP_CONV_WGRAD, OP_CONV_DGRAD, OP_SGD, OP_BIAS_GRAD, OP_BIAS_FINISH
 };
 
 struct Tensor {
@@ -44,6 +44,9 @@ struct Op {
     bool fuse_sgd = false;  // weight gradient that applies the SGD update itself (fp32 master weights at t6, bf16 copy at
                             // t7); it runs after the layer's data gradient, which still needs the old weights
     size_t t6 = 0, t7 = 0;
+    bool colsum = false;    // data gradient whose epilogue also leaves per-tile column sums of its (masked) output at t8:
+                            // the bias gradient of the layer below, finished by the OP_BIAS_FINISH operation behind it
+    size_t t8 = 0;
     int N = 0, H = 0, W = 0, C = 0, win = 0, st = 0;  // pooling / softmax shapes
     size_t n = 0;
     const char* kernel = "";  // kernel instantiation the operation launches
@@ -89,6 +92,7 @@ struct wap_step_plan {
     size_t w32_off = 0, dw_off = 0, wb_off = 0;
     mutable std::vector<hipEvent_t> events;  // cached by wap_step_time
     PackJobs packjobs = {};                  // every weight repacking of the step, run as one kernel
+    ColsumJobs colsumjobs = {};              // every bias gradient finished from per-tile column sums, run as one pair
     mutable bool ran_once = false;           // an eager step has completed its launches (kernel attributes are set)
     hipGraph_t graph = nullptr;
     hipGraphExec_t graph_exec = nullptr;
@@ -125,7 +129,8 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
                                    op.prepacked ? (const void*)(base + op.t4) : nullptr,
                                    op.has_pool ? (bf16_t*)(base + op.t3) : nullptr,
                                    op.has_pool ? (uint8_t*)(base + op.t5) : nullptr,
-                                   op.unpool ? (const uint8_t*)(base + op.t5) : nullptr);
+                                   op.unpool ? (const uint8_t*)(base + op.t5) : nullptr,
+                                   op.colsum ? (float*)(base + op.t8) : nullptr);
         case OP_CONV_WGRAD:
         case OP_FC_DW: {
             const SgdFuse sgd = {(float*)(base + op.t6), (bf16_t*)(base + op.t7), p->lr};
@@ -148,6 +153,8 @@ int run_op(const wap_step_plan* p, const Op& op, unsigned char* base, hipStream_
                                        (float*)(base + op.t2), (float*)(base + op.t3), (bf16_t*)(base + op.t4), st);
         case OP_BIAS_GRAD:
             return launch_bias_grad(op.n, op.C, (const bf16_t*)(base + op.t0), (float*)(base + op.t1), (float*)ws, st);
+        case OP_BIAS_FINISH:  // the per-tile column sums that the data gradients left -> bias gradients, all layers at once
+            return launch_colsum_f32_multi(p->colsumjobs, base, st);
         case OP_SGD:
             return launch_sgd(op.n, (float*)(base + op.t0), (const float*)(base + op.t1), p->lr,
                               (bf16_t*)(base + op.t2), st);
@@ -309,6 +316,23 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
         if (need > ws_need) ws_need = need;
         p->ops.push_back(op);
     };
+    // The same gradient where the data gradient that produced dy (ReLU derivative applied in its epilogue) can leave
+    // per-tile column sums of what it stores: no pass over dy at all; the (small) partial rows of all such layers are
+    // added up by one operation at the end of the backward pass.
+    struct ColsumReq { size_t op_index; int li, rows, cols; };
+    std::vector<ColsumReq> colsum_reqs;
+    auto try_fuse_bias_grad = [&](int li) -> bool {
+        if (!with_bias || keep || p->ops.empty() || (int)colsum_reqs.size() >= kMaxColsumJobs) return false;
+        Op& prod = p->ops.back();
+        if ((prod.kind != OP_CONV_DGRAD && prod.kind != OP_FC_DX) || !prod.has_mask || prod.has_pool) return false;
+        const int rows = fwd_like_colsum_rows(prod.gg, prod.gp);
+        if (rows == 0 || prod.gg.Ncols != (int)bcount[li] || (prod.gg.Ncols % 4) != 0) return false;
+        prod.colsum = true;
+        prod.name += "+bias_grad";
+        prod.bytes += 4.0 * rows * prod.gg.Ncols;
+        colsum_reqs.push_back({p->ops.size() - 1, li, rows, prod.gg.Ncols});
+        return true;
+    };
     auto set_bias = [&](int li) {
         if (!with_bias) return;
         Op& f = p->ops.back();
@@ -466,6 +490,9 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             p->ops.push_back(op);
             g_cur = op.t2;
         }
+        // bias gradient: from the epilogue of the data gradient that produced g_cur where that kernel can (it applied
+        // this layer's ReLU derivative and is the last operation so far), else a pass over g_cur further down
+        const bool bias_fused = (unpool || relu_done) && try_fuse_bias_grad(i);
         size_t x_in = i == 0 ? t_input : (convs[i - 1].pool_win ? pool_y[i - 1] : conv_y[i - 1]);
         push_wgrad(OP_CONV_WGRAD, nm + ".wgrad", geom_conv_wgrad(d), x_in, g_cur, i);
         if (unpool) {
@@ -477,7 +504,7 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             wgop.bytes += 3.0 * pool_y_elems[i] - 2.0 * conv_y_elems[i];
         }
         // routing a pooled gradient to the argmax pixels keeps every column's sum: the pooled tensor serves as well
-        push_bias_grad(i, (unpool ? pool_y_elems[i] : conv_y_elems[i]) / d.K, g_cur);
+        if (!bias_fused) push_bias_grad(i, (unpool ? pool_y_elems[i] : conv_y_elems[i]) / d.K, g_cur);
         if (i > 0) {  // the gradient w.r.t. the input image is not needed
             if (!keep) gsel = (g_cur == gbuf[0]) ? 1 : 0;
             std::string in_name = "g." + lname(i - 1) + (convs[i - 1].pool_win ? ".pool.y" : ".y");
@@ -504,6 +531,24 @@ int wap_step_plan_create(const char* net, int32_t minibatch, int32_t image, floa
             }
             g_cur = g_in;
         }
+    }
+
+    // ---- bias gradients left as per-tile column sums by the data gradients: one region per layer, finished together ----
+    if (!colsum_reqs.empty()) {
+        double bytes = 0;
+        for (const ColsumReq& rq : colsum_reqs) {
+            const size_t part = p->add("bias.colsum." + lname(rq.li), (size_t)rq.rows * rq.cols * sizeof(float));
+            const size_t part2 = p->add("bias.colsum2." + lname(rq.li),
+                                        (size_t)colsum_f32_chunks((size_t)rq.rows) * rq.cols * sizeof(float));
+            p->ops[rq.op_index].t8 = part;
+            colsum_jobs_add(p->colsumjobs, rq.rows, rq.cols, part, part2, p->dw_off + boff[rq.li] * 4);
+            bytes += 4.0 * rq.rows * rq.cols + 4.0 * rq.cols;
+        }
+        Op op;
+        op.kind = OP_BIAS_FINISH; op.name = "bias_grad_finish";
+        op.kernel = "colsum_f32_multi_kernel";
+        op.bytes = bytes;
+        p->ops.push_back(op);
     }
 
     // ---- update ----

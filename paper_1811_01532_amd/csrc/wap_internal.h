@@ -106,8 +106,26 @@ int launch_fwd_like(const GemmGeom& g, bool b_tr, const GemmPlan& plan, const bf
                     const void* prepacked = nullptr,     // weights already in packed order: skip the repacking
                     bf16_t* pool_y = nullptr,            // 2x2 / stride-2 max-pool of the output from the same epilogue
                     uint8_t* pool_am = nullptr,          // (only where fwd_like_fuses_pool; `out` may then be NULL)
-                    const uint8_t* unpool_am = nullptr); // A is the gradient of the 2x2 / stride-2 pooled tensor and this the
+                    const uint8_t* unpool_am = nullptr,  // A is the gradient of the 2x2 / stride-2 pooled tensor and this the
                                                          // pool's argmax (only where fwd_like_fuses_unpool)
+                    float* colsum = nullptr);            // column sums of the stored output, one partial row per pixel
+                                                         // tile (only where fwd_like_colsum_rows > 0; not with pool_y)
+int fwd_like_colsum_rows(const GemmGeom& g, const GemmPlan& plan);  // 0: the plan's kernel cannot emit column sums
+// Fixed-order column sums of fp32 matrices [rows][cols] (cols % 4 == 0), all of a step in one pair of launches; byte
+// offsets are relative to one base pointer; part2 holds colsum_f32_chunks(rows) x cols floats per matrix.
+struct ColsumJob {
+    int rows, cols, chunks;
+    size_t part_off, part2_off, out_off;
+};
+constexpr int kMaxColsumJobs = 24;
+struct ColsumJobs {
+    int n;
+    int first[kMaxColsumJobs + 1];  // first work-group of each job in the first-stage grid
+    ColsumJob job[kMaxColsumJobs];
+};
+int colsum_f32_chunks(size_t rows);
+int colsum_jobs_add(ColsumJobs& js, int rows, int cols, size_t part_off, size_t part2_off, size_t out_off);  // -1: full / bad
+int launch_colsum_f32_multi(const ColsumJobs& js, void* base, hipStream_t st);
 bool fwd_like_fuses_unpool(const GemmGeom& g, const GemmPlan& plan);
 bool fwd_like_fuses_pool(const GemmGeom& g, const GemmPlan& plan);
 bool fwd_like_packs_weights(const GemmPlan& plan);
@@ -188,7 +206,8 @@ int tile64_width(const GemmGeom& g);  // 0: not applicable
 const char* tile64_kernel_name(const GemmGeom& g, bool unpool);
 bool tile64_fuses_unpool(const GemmGeom& g);
 int launch_tile64(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
-                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am);
+                  hipStream_t st, const bf16_t* mask, bf16_t* pool_y, uint8_t* pool_am, const uint8_t* unpool_am,
+                  float* colsum = nullptr);
 
 // stride-1 convolution with double-buffered 32-channel patch slices: 2-D, strip and flat tiles (conv_tile2d.hip;
 // it hands the shapes of conv_tile64.hip on to that kernel)
@@ -197,7 +216,9 @@ bool tile2d_preferred(const GemmGeom& g);
 const char* tile2d_kernel_name(const GemmGeom& g, bool unpool);
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
                   hipStream_t st, const bf16_t* mask = nullptr, bf16_t* pool_y = nullptr, uint8_t* pool_am = nullptr,
-                  const uint8_t* unpool_am = nullptr);
+                  const uint8_t* unpool_am = nullptr,
+                  float* colsum = nullptr);  // [tile2d_colsum_rows][Ncols] column sums of the stored (masked) output
+int tile2d_colsum_rows(const GemmGeom& g);
 bool tile2d_fuses_pool(const GemmGeom& g);
 bool tile2d_fuses_unpool(const GemmGeom& g);
 
