@@ -594,7 +594,9 @@ struct TileCfg {
                               // 192 pixels x 64 channels (2 x 3 fragments) for thin outputs on maps no 2-D tile divides
     int RWB, buf_bytes;       // LDS layout: byte stride of a patch row, bytes of one patch buffer
     size_t smem;              // dynamic LDS of the launch: two patch buffers, or the staged output tile if larger
+    int fm;                   // variant 2: 32-pixel fragments per wavefront (7 or 2: tiles of 224 or 64 pixels)
 };
+int tile_pixels(const TileCfg& c) { return c.variant == 3 ? 192 : c.variant == 2 ? 32 * c.fm : c.variant == 1 ? 224 : 256; }
 // most patch pixels (rows of OW + S - 1) any bm-pixel raster-order tile of this geometry loads
 int max_flat_patch(const GemmGeom& g, int bm) {
     const int PH = g.OH + g.R - 1, PW = g.OW + g.S - 1;
@@ -635,7 +637,7 @@ int conflict_free_stride(int width, int S) { return width * PITCH + ((S - 1) * P
 
 // LDS layout of a tile shape: the conflict-free row stride if two work-groups per CU still fit, else dense rows.
 bool lds_layout(const GemmGeom& g, TileCfg* c) {
-    const int bm = c->variant == 3 ? 192 : c->variant >= 1 ? 224 : 256;
+    const int bm = tile_pixels(*c);
     const int bn = c->variant == 3 ? 64 : c->variant >= 1 ? 128 : 64 * c->fn;
     const size_t stage = (size_t)bm * (bn * 2 + 16);
     const bool flat = c->variant >= 2;
@@ -665,7 +667,7 @@ bool lds_layout(const GemmGeom& g, TileCfg* c) {
 // per 64-channel slice of a 3x3 filter whatever the minibatch, so the flat tiles win only once the layer holds
 // enough work.
 bool flat64_fits(const GemmGeom& g) {
-    TileCfg c = {1, 0, 0, 3, 0, 0, 0};
+    TileCfg c = {1, 0, 0, 3, 0, 0, 0, 0};
     return g.M >= 192 * 4 && max_flat_patch(g, 192) <= MAX_PATCH_FLAT64 && lds_layout(g, &c);
 }
 bool flat64_wins_small_batch(const GemmGeom& g) {
@@ -680,34 +682,48 @@ bool flat64_wins_small_batch(const GemmGeom& g) {
 }
 // Tile shape for this geometry (width must divide the map, patch must fit), fn = 0 if none.
 TileCfg tile_cfg(const GemmGeom& g) {
-    TileCfg none = {0, 0, 0, 0, 0, 0, 0};
+    TileCfg none = {0, 0, 0, 0, 0, 0, 0, 0};
     TileCfg c = none;
     if ((g.Ncols % 64) != 0) return none;
     const bool tiles128 = (g.Ncols % 128) == 0;  // 2-D tiles of 128 channels (64 output channels: conv_tile64.hip)
     for (int tw : {32, 16, 8}) {
         const int th = 256 / tw;
         if (tiles128 && (g.OH % th) == 0 && (g.OW % tw) == 0 && (th + g.R - 1) * (tw + g.S - 1) <= MAX_PATCH) {
-            c = {2, tw, th, 0, 0, 0, 0};
+            c = {2, tw, th, 0, 0, 0, 0, 0};
             if (lds_layout(g, &c)) return c;
             c = none;
         }
     }
     // maps of 28k x 8j pixels (56 x 56): 8 x 28 tiles, one 224-pixel strip per wavefront, 128-channel tiles
     if ((g.Ncols % 128) == 0 && (g.OW % 28) == 0 && (g.OH % 8) == 0 && (8 + g.R - 1) * (28 + g.S - 1) <= MAX_PATCH) {
-        c = {1, 28, 8, 1, 0, 0, 0};
+        c = {1, 28, 8, 1, 0, 0, 0, 0};
         if (!lds_layout(g, &c)) c = none;
     }
-    if (c.fn == 0 && (g.Ncols % 128) == 0 && g.M >= 224 * 4 && max_flat_patch(g, 224) <= MAX_PATCH_FLAT) {
-        c = {1, 0, 0, 2, 0, 0, 0};
-        if (!lds_layout(g, &c)) c = none;
+    // Flat 128-channel tiles: 224 pixels per tile while that puts a work-group on at least three quarters of the CUs,
+    // else 64 pixels (the serial reduction of a tile is what a small layer waits for: a short tile shortens every
+    // reduction step four-fold and puts more work-groups on the chip; the weight stream per pixel grows, which a small
+    // layer can afford).  Measured: conv4_2 at minibatch 8 55 -> 44 us, conv5_1 at 32 54 -> 44 us, at 16 37 -> 33 us;
+    // 128-pixel tiles lost to 224-pixel ones wherever both applied (conv5_1 at 64: 68 vs 64 us).  Short flat tiles
+    // also replace the strips where those leave the chip under-filled.
+    const long strips = c.fn ? (long)(g.M / 224) * (g.Ncols / 128) : 0;
+    if ((c.fn == 0 || strips < kNumCU * 3 / 4) && (g.Ncols % 128) == 0 && g.M >= 64 * 4) {
+        for (int fm : {7, 2}) {
+            const int bm = 32 * fm;
+            const long wgs = (long)((g.M + bm - 1) / bm) * (g.Ncols / 128);
+            if (max_flat_patch(g, bm) > MAX_PATCH_FLAT || (fm > 2 && wgs < kNumCU * 3 / 4)) continue;
+            if (c.fn != 0 && wgs <= strips) break;  // no better filled than the strips
+            TileCfg f = {1, 0, 0, 2, 0, 0, 0, fm};
+            if (lds_layout(g, &f)) { c = f; break; }
+        }
     }
     // 192-pixel x 64-channel flat tiles where none of the above applies (64 or 192 output channels on maps no 2-D
     // tile divides), and for wide outputs at a small minibatch where they beat the generic kernel
     const bool use64 = (c.fn == 0 && flat64_fits(g)) ||
                        (c.fn != 0 && c.variant >= 1 && c.variant <= 2 &&
-                        (long)((g.M + 223) / 224) * (g.Ncols / 128) < kNumCU * 3 / 4 && flat64_wins_small_batch(g));
+                        (long)((g.M + tile_pixels(c) - 1) / tile_pixels(c)) * (g.Ncols / 128) < kNumCU * 3 / 4 &&
+                        flat64_wins_small_batch(g));
     if (use64) {
-        c = {1, 0, 0, 3, 0, 0, 0};
+        c = {1, 0, 0, 3, 0, 0, 0, 0};
         if (!lds_layout(g, &c)) c = none;
     }
     return c;
@@ -735,7 +751,7 @@ bool tile2d_preferred(const GemmGeom& g) {
         const long t3 = (long)((g.M + 191) / 192) * (g.Ncols / 64);
         return g.Ncols == 64 ? t3 >= 48 : (t3 >= 200 || flat64_wins_small_batch(g));
     }
-    return (long)((g.M + 223) / 224) * (g.Ncols / 128) >= kNumCU * 3 / 4;
+    return (long)((g.M + tile_pixels(c) - 1) / tile_pixels(c)) * (g.Ncols / 128) >= kNumCU * 3 / 4;
 }
 
 const char* tile2d_kernel_name(const GemmGeom& g, bool unpool) {
@@ -748,8 +764,10 @@ const char* tile2d_kernel_name(const GemmGeom& g, bool unpool) {
                                    {"conv_tile2d_kernel<1,0,7,1,true,false>", "conv_tile2d_kernel<1,0,7,1,true,true>"}};
     static const char* n3[2][2] = {{"conv_tile2d_kernel<1,0,3,2,false,false>", "conv_tile2d_kernel<1,0,3,2,false,true>"},
                                    {"conv_tile2d_kernel<1,0,3,2,true,false>", "conv_tile2d_kernel<1,0,3,2,true,true>"}};
+    static const char* n22[2][2] = {{"conv_tile2d_kernel<1,0,2,1,false,false>", "conv_tile2d_kernel<1,0,2,1,false,true>"},
+                                    {"conv_tile2d_kernel<1,0,2,1,true,false>", "conv_tile2d_kernel<1,0,2,1,true,true>"}};
     if (c.variant == 1) return n1[u][t9];
-    if (c.variant == 2) return n2[u][t9];
+    if (c.variant == 2) return c.fm == 7 ? n2[u][t9] : n22[u][t9];
     if (c.variant == 3) return n3[u][t9];
     static const char* names[2][2][3] = {
         {{"conv_tile2d_kernel<2,32,4,2,false,false>", "conv_tile2d_kernel<2,16,4,2,false,false>", "conv_tile2d_kernel<2,8,4,2,false,false>"},
@@ -772,7 +790,7 @@ bool tile2d_fuses_unpool(const GemmGeom& g) {
 int tile2d_colsum_rows(const GemmGeom& g) {
     if (const int tw = tile64_width(g)) return (g.M / (g.OH * g.OW)) * (g.OW / tw) * (g.OH / (256 / tw));
     const TileCfg c = tile_cfg(g);
-    if (c.variant >= 2) return (g.M + (c.variant == 3 ? 192 : 224) - 1) / (c.variant == 3 ? 192 : 224);
+    if (c.variant >= 2) return (g.M + tile_pixels(c) - 1) / tile_pixels(c);
     return (g.M / (g.OH * g.OW)) * (g.OW / c.tw) * (g.OH / c.th);
 }
 
@@ -783,7 +801,7 @@ bool tile2d_fuses_pool(const GemmGeom& g) {
     const TileCfg c = tile_cfg(g);  // even tile origin and size, whole windows per staging pass
     if (c.variant == 0 || c.variant == 1) return true;  // strips stage the whole 224 x 128 tile in one pass
     // flat 224 x 128 tiles: whole row pairs per tile
-    return c.variant == 2 && (g.OH % 2) == 0 && (g.OW % 2) == 0 && (224 % (2 * g.OW)) == 0;
+    return c.variant == 2 && (g.OH % 2) == 0 && (g.OW % 2) == 0 && (tile_pixels(c) % (2 * g.OW)) == 0;
 }
 
 int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const float* bias, bool relu, bf16_t* out,
@@ -813,7 +831,7 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
     ta.RWB = c.RWB;
     ta.buf_bytes = c.buf_bytes;
     if (c.variant >= 2) {
-        const int bm = c.variant == 3 ? 192 : 224;
+        const int bm = tile_pixels(c);
         ta.tiles_x = ta.tiles_y = ta.tiles_img = 1;
         ta.tiles_m = (g.M + bm - 1) / bm;
         ta.PH = g.OH + g.R - 1;
@@ -843,7 +861,8 @@ int launch_tile2d(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
     ta.dRW = make_fastdiv((uint32_t)ta.RW);
     const size_t smem = c.smem;
     if (c.variant == 1) return launch_tile2d_t<1, 28, 7, 1>(ta, smem, st);
-    if (c.variant == 2) return launch_tile2d_t<1, 0, 7, 1>(ta, smem, st);
+    if (c.variant == 2 && c.fm == 7) return launch_tile2d_t<1, 0, 7, 1>(ta, smem, st);
+    if (c.variant == 2) return launch_tile2d_t<1, 0, 2, 1>(ta, smem, st);
     if (c.variant == 3) return launch_tile2d_t<1, 0, 3, 2>(ta, smem, st);
     const int TW = c.tw;  // 2-D tiles: two channel blocks per wavefront, 128-channel tiles
     if (TW == 32) return launch_tile2d_t<2, 32, 4, 2>(ta, smem, st);
