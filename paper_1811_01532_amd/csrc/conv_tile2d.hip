@@ -340,21 +340,16 @@ __global__ __launch_bounds__(NT, 2) void conv_tile2d_kernel(const TArgs a) {
         }
     };
     // issue order of a step: one fragment read behind every FN MFMAs; the step's VMEM loads (weights of a later tap,
-    // the next patch slice) ride behind the MFMA groups from group LEAD on, one or more per group
+    // the next patch slice) ride in front of the first MFMA groups, one or more per group (where they sit within the
+    // step measured the same: first, third or fifth group)
     auto pin_step = [&](auto vmem_tag) {
         constexpr int NV = decltype(vmem_tag)::value;  // VMEM loads to place
-#ifndef WAP_LEAD
-#define WAP_LEAD 0
-#endif
-        constexpr int LEAD = NV > 0 && FM > WAP_LEAD ? WAP_LEAD : 0;
-        constexpr int SLOTS = FM - LEAD;
-        constexpr int PER = NV > 0 ? (NV + SLOTS - 1) / SLOTS : 0;
+        constexpr int PER = NV > 0 ? (NV + FM - 1) / FM : 0;
 #pragma unroll
         for (int q = 0; q < FM; ++q) {
-            if (NV > 0 && q >= LEAD && (q - LEAD) * PER < NV)
-                __builtin_amdgcn_sched_group_barrier(0x020, PER, 0);  // VMEM read
-            __builtin_amdgcn_sched_group_barrier(0x008, FN, 0);      // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // DS read
+            if (NV > 0 && q * PER < NV) __builtin_amdgcn_sched_group_barrier(0x020, PER, 0);  // VMEM read
+            __builtin_amdgcn_sched_group_barrier(0x008, FN, 0);                                // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                 // DS read
         }
     };
 
