@@ -374,6 +374,26 @@ def main():
     del b2, p2
     torch.cuda.empty_cache()
 
+    # ---- what the matrix pipe of this device sustains (clock under load), measured beside the published peak ----
+    log("measuring the MFMA ceiling")
+    cs = torch.empty(wap.wap_mfma_ceiling_scratch_bytes() + 256, dtype=torch.uint8, device="cuda")
+    ceil_rows = []
+    for data, feed, label in ((0, 0, "constant operands, registers only"), (1, 0, "random operands, registers only"),
+                              (1, 1, "random operands, LDS + L2 operand feed of the forward kernels")):
+        r = wap.wap_measure_mfma_ceiling(data, feed, 6000, cs)
+        ceil_rows.append({"data": "random" if data else "constant", "feed": "lds+l2" if feed else "registers",
+                          "what": label, "tflops": round(r.tflops, 1), "clock_ghz": round(r.clock_ghz, 3),
+                          "frac_of_bf16_peak": round(r.tflops / PEAK_BF16, 4)})
+    del cs
+    out["mfma_ceiling"] = {"rows": ceil_rows,
+                           "note": "wap_measure_mfma_ceiling: a loop of v_mfma_f32_32x32x16_bf16 on every CU; the chip "
+                                   "lowers its clock under load, so these measured rates, not the published peak, bound "
+                                   "what a kernel can reach on this device"}
+    fed = ceil_rows[2]["tflops"]
+    if roof.get("bound") == "mfma" and fed > 0:
+        roof["frac_of_measured_ceiling"] = round(roof["achieved"] / fed, 4)
+        roof["measured_ceiling_tflops"] = fed
+
     md = []
     if not a.no_table:
         # ---- step-level utilisation versus per-GPU minibatch, both networks ----
@@ -484,6 +504,10 @@ def main():
         for r in table:
             md.append(f"| {r['net']} | {r['minibatch']} | {r['ms_per_step']} | {r['tflops']} | "
                       f"{r['frac_of_bf16_peak']} | {r['images_per_s']} |")
+        md.append("\n## Measured ceiling of the matrix pipe (wap_measure_mfma_ceiling: MFMA loop on every CU, clock read in the kernel)\n")
+        md.append("| operands | operand feed | TFLOP/s | clock GHz | frac of bf16 peak |\n|---|---|---|---|---|")
+        for r in out["mfma_ceiling"]["rows"]:
+            md.append(f"| {r['data']} | {r['feed']} | {r['tflops']} | {r['clock_ghz']} | {r['frac_of_bf16_peak']} |")
         md.append("\n## Workload analysis (Eq. 1): measured t_c at minibatch B/d, analytic ring all-reduce t_s\n")
         md.append("| net | global minibatch | t_estimate ms by d | chosen d |\n|---|---|---|---|")
         for r in wau_rows:
@@ -535,6 +559,8 @@ def main():
         line["util_table"] = {"columns": ["net", "minibatch", "ms_per_step", "tflops", "frac_of_bf16_peak"],
                               "rows": [[r["net"], r["minibatch"], r["ms_per_step"], r["tflops"], r["frac_of_bf16_peak"]]
                                        for r in out["util_table"]]}
+    if "mfma_ceiling" in out:
+        line["mfma_ceiling_tflops"] = {f"{r['data']}/{r['feed']}": [r["tflops"], r["clock_ghz"]] for r in out["mfma_ceiling"]["rows"]}
     if "gradients_stored" in out:
         line["gradients_stored_ms_per_step"] = round(out["gradients_stored"]["ms_per_step"], 4)
     line["detail"] = {"json": os.path.relpath(a.detail_out, ROOT) if a.detail_out else None,

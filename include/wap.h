@@ -13,8 +13,8 @@
  *   - extern "C"; return a wap_status; never throw, never abort.
  *   - Every tensor pointer is DEVICE memory owned by the caller, 16-byte aligned, and must stay
  *     alive until the work enqueued on `stream` has finished.  The library keeps no reference
- *     after return, allocates and frees no device memory and (except wap_profile_layer and the
- *     step-plan timing helper) never synchronises.
+ *     after return, allocates and frees no device memory and (except wap_profile_layer,
+ *     wap_measure_mfma_ceiling and the step-plan timing helper) never synchronises.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *   - bf16 tensors are arrays of 16-bit bfloat16 bit patterns.  Accumulation is fp32.
  *     Conversions to bf16 round to nearest, ties to even.
@@ -257,6 +257,27 @@ int wap_profile_scratch_bytes(int kind /*0 conv, 1 fc*/, const void* desc, const
 int wap_profile_layer(int kind, const void* desc, const int32_t* minibatches, int32_t n_mb,
                       int32_t warmup, int32_t iters, void* scratch, size_t scratch_bytes,
                       void* stream, wap_profile_row* rows_out, int32_t rows_cap, int32_t* rows_written);
+
+/* What the bf16 matrix pipe of this device sustains, measured: the yardstick beside the published peak for the
+ * utilisation figures above (Table 1; the measured t_c of Eq. 1, Section 3.2.1).  The chip lowers its clock under
+ * load, by an amount that depends on the operand values and on what else runs per MFMA, so no kernel can reach
+ * clock_max x units; this times a loop of v_mfma_f32_32x32x16_bf16 on every CU (two work-groups of four
+ * wavefronts per CU, 7 independent accumulators per wavefront) and reports its rate and the average shader clock.
+ *   data: 0 = every operand 1.0; 1 = pseudo-random bf16 operands (random sign and mantissa, exponents 2^-3 .. 2^0).
+ *   feed: 0 = operands stay in registers; 1 = the operand traffic of the forward / data-gradient kernels' main
+ *         loop (per 7 MFMAs seven 16-byte LDS reads and one 16-byte L2-resident global load).
+ *   iters: loop trips per wavefront (7 MFMAs each), 1 .. 2^20; a warm-up launch of iters / 8 + 1 trips runs first.
+ * `scratch`: device memory, wap_mfma_ceiling_scratch_bytes() bytes, 256-byte aligned (overwritten).  Synchronises
+ * `stream` before returning.  WAP_EINVAL for arguments outside the ranges above, WAP_EWORKSPACE for the scratch. */
+typedef struct wap_mfma_ceiling_row {
+    int32_t data, feed;
+    double tflops;     /* 2 * 32 * 32 * 16 FLOP per MFMA over the timed launch */
+    double clock_ghz;  /* shader clock counter against the constant 100 MHz counter, read inside the kernel */
+    double us;         /* duration of the timed launch (HIP events) */
+} wap_mfma_ceiling_row;
+size_t wap_mfma_ceiling_scratch_bytes(void);
+int wap_measure_mfma_ceiling(int32_t data, int32_t feed, int32_t iters, void* scratch, size_t scratch_bytes,
+                             void* stream, wap_mfma_ceiling_row* out);
 
 /* ---- the workload analysis unit's decision (Section 3.2.1): how many GPUs to divide the workload over ----
  * Evaluates Eq. 1, t_estimate(d) = sum over layers of { t_c(l, d) + t_s(l, d) }, for d = 1..max_gpus and

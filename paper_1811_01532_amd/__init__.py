@@ -56,6 +56,11 @@ class ProfileRow(ctypes.Structure):
                 ("frac_of_hbm_peak", ctypes.c_double), ("bound", ctypes.c_int32), ("reps_per_sample", ctypes.c_int32)]
 
 
+class MfmaCeilingRow(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_int32), ("feed", ctypes.c_int32), ("tflops", ctypes.c_double),
+                ("clock_ghz", ctypes.c_double), ("us", ctypes.c_double)]
+
+
 _lib = None
 
 
@@ -70,6 +75,7 @@ def lib():
         _lib.wap_debug_force.restype = None
         _lib.wap_step_flops.restype = ctypes.c_double
         _lib.wap_step_plan_destroy.restype = None
+        _lib.wap_mfma_ceiling_scratch_bytes.restype = ctypes.c_size_t
     return _lib
 
 
@@ -277,6 +283,19 @@ def wap_profile_layer(kind, desc, minibatches, warmup, iters, scratch, stream=No
                                    ctypes.c_size_t(_nbytes(scratch)), _stream(stream), rows, 3 * n,
                                    ctypes.byref(written)))
     return [rows[i] for i in range(written.value)]
+
+
+def wap_mfma_ceiling_scratch_bytes():
+    return int(lib().wap_mfma_ceiling_scratch_bytes())
+
+
+def wap_measure_mfma_ceiling(data, feed, iters, scratch, stream=None):
+    """Measured rate of the bf16 matrix pipe (data 0/1: constant / random operands; feed 0/1: registers only / the
+    forward kernels' operand traffic); returns a MfmaCeilingRow."""
+    row = MfmaCeilingRow()
+    _check(lib().wap_measure_mfma_ceiling(int(data), int(feed), int(iters), _ptr(scratch),
+                                          ctypes.c_size_t(_nbytes(scratch)), _stream(stream), ctypes.byref(row)))
+    return row
 
 
 class LinkModel(ctypes.Structure):

@@ -136,3 +136,29 @@ def test_step_time_is_bracketed_by_its_layer_times():
     step_us = (time.perf_counter() - t0) / steps * 1e6
     print(f"[info] step {step_us:.1f} us, sum of layer passes {total:.1f} us, longest pass {longest:.1f} us", flush=True)
     assert longest <= step_us <= 2.0 * total
+
+
+def test_mfma_ceiling_rows():
+    """The measured ceiling of the matrix pipe: rates below the published peak, clocks inside the chip's range,
+    constant operands no slower than random ones, register-only no slower than the LDS / L2-fed loop, and the rate
+    consistent with the clock the kernel read (7 MFMAs of 32 cycles per trip, two wavefronts per SIMD)."""
+    import paper_1811_01532_amd as wap
+    scratch = torch.empty(wap.wap_mfma_ceiling_scratch_bytes() + 256, dtype=torch.uint8, device="cuda")
+    rows = {}
+    for data in (0, 1):
+        for feed in (0, 1):
+            print(f"[case] mfma ceiling data={data} feed={feed}", flush=True)
+            r = wap.wap_measure_mfma_ceiling(data, feed, 4000, scratch)
+            assert (r.data, r.feed) == (data, feed)
+            assert 300.0 < r.tflops < PEAK_TF
+            assert 0.8 < r.clock_ghz < 2.6
+            assert r.us > 0.0
+            # at most one MFMA per SIMD every 32 cycles: the rate cannot exceed what the measured clock allows
+            assert r.tflops <= 1.05 * PEAK_TF * r.clock_ghz / 2.4
+            rows[(data, feed)] = r
+    assert rows[(1, 0)].tflops <= 1.03 * rows[(0, 0)].tflops
+    assert rows[(1, 1)].tflops <= 1.03 * rows[(1, 0)].tflops
+    with pytest.raises(wap.WapError):
+        wap.wap_measure_mfma_ceiling(2, 0, 100, scratch)
+    with pytest.raises(wap.WapError):
+        wap.wap_measure_mfma_ceiling(0, 0, 100, scratch[:4096])
