@@ -55,6 +55,13 @@ CASES = [
     ("wgrad_patch_pad0_w30", (2, 34, 32, 64, 64, 3, 3, 1, 0), (-1, -1, -1)),
     ("wgrad_patch_w13_partly_masked_tile_rows", (3, 13, 13, 192, 128, 3, 3, 1, 1), (-1, -1, -1)),
     ("wgrad_patch_h22_w12_partly_masked_even", (2, 22, 12, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
+    # the remaining step maps of the patch weight gradient (block steps on 20 / 24 / 28-wide maps with 64 output
+    # channels, half-row steps with 128, a ragged last tile row of the 4-row tiles), each also with the pooled dy
+    ("wgrad_patch_blocks_w20_k64", (2, 12, 20, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
+    ("wgrad_patch_blocks_w24_k64_ragged_rows", (2, 10, 24, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
+    ("wgrad_patch_blocks_w28_k64", (2, 28, 28, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
+    ("wgrad_patch_halfrows_w32_k128", (2, 12, 32, 64, 128, 3, 3, 1, 1), (-1, -1, -1)),
+    ("wgrad_patch_blocks_w20_k128_two_tiles_per_row", (1, 12, 40, 128, 128, 3, 3, 1, 1), (-1, -1, -1)),
     # backward through a 2x2 pool routed in the loaders: flat data-gradient tiles, two dy blocks per wavefront
     ("unpool_flat_w14_c128_k128", (5, 14, 14, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
     ("unpool_w112_c64_k128", (1, 32, 112, 64, 128, 3, 3, 1, 1), (-1, -1, -1)),
