@@ -82,8 +82,11 @@ __device__ __forceinline__ u32x4 unpool_select8(u32x4 v, u32x2 am, unsigned code
     return v;
 }
 
-// TW: tile width in pixels (the tile is 256 / TW rows high).  UP: pooled input operand.
-template <int TW, bool UP>
+// TW: tile width in pixels (the tile is 256 / TW rows high).  UP: pooled input operand.  T9: 3x3 filter, the nine
+// taps of a slice as straight-line code (every fragment address an immediate offset, the two weight register sets
+// alternating by tap instead of being copied, no loop bookkeeping: the time of these kernels follows their
+// instruction count).
+template <int TW, bool UP, bool T9>
 __global__ __launch_bounds__(NT, 3) void conv_tile64_kernel(const T64Args a) {
     constexpr int TH = BM / TW;
     constexpr int PV = (MAX_PATCH * 8 + NT - 1) / NT;  // 16-byte patch vectors per thread
@@ -161,17 +164,17 @@ __global__ __launch_bounds__(NT, 3) void conv_tile64_kernel(const T64Args a) {
 #pragma unroll
     for (int j = 0; j < FM; ++j) {
         const int idx = (pg * FM + j) * 32 + (lane & 31);
-        frow[j] = ((idx / TW) * a.RW + (idx % TW)) * PITCH + (lane >> 5) * 16;
+        frow[j] = ((idx / TW) * (T9 ? TW + 2 : a.RW) + (idx % TW)) * PITCH + (lane >> 5) * 16;
     }
 
     // ---- weights: packed [channel block of 32][reduction step of 16][lane][8] ----
     const unsigned ksteps = (unsigned)g.Kred / 16u;
     const unsigned wrow = ((unsigned)cg * ksteps * 64u + (unsigned)lane) * 16u;
     auto load_w = [&](int cs, int tap, bf16x8 (&w)[4]) {
-        const unsigned koff = ((unsigned)(tap * g.IC + cs * BK) / 16u) * 1024u;
+        const unsigned koff = ((unsigned)(tap * g.IC + cs * BK) / 16u) * 1024u;  // uniform: rides in the scalar offset
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-            w[ks] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rsrcW, wrow + koff + (unsigned)ks * 1024u, 0, 0));
+            w[ks] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rsrcW, wrow + (unsigned)ks * 1024u, koff, 0));
     };
 
     f32x16 acc[FM];
@@ -221,15 +224,11 @@ __global__ __launch_bounds__(NT, 3) void conv_tile64_kernel(const T64Args a) {
 #pragma unroll
         for (int j = 0; j < FM; ++j) fa[0][j] = *reinterpret_cast<const bf16x8*>(smem + frow[j]);
         __builtin_amdgcn_s_setprio(1);
-        int r = 0, s = 0;
-        for (int tap = 0; tap < RS; ++tap) {
-            const bool last = tap + 1 == RS;
-            int s1 = s + 1, r1 = r;
-            if (s1 == g.S) { s1 = 0; r1 = r + 1; }
-            const int tapoff = (r * a.RW + s) * PITCH;
-            const int tapoff1 = last ? tapoff : (r1 * a.RW + s1) * PITCH;  // after the last tap the read is discarded
+        // one tap: 4 reduction steps of 16 channels x FM fragments; the weights of the following tap are fetched
+        // meanwhile, and the last step's fragment reads already belong to that tap
+        auto tap_body = [&](const bf16x8 (&wc)[4], bf16x8 (&wn)[4], int tapoff, int tapoff1, int ncs_, int ntap) {
             __builtin_amdgcn_sched_barrier(0);
-            load_w(last ? cs1 : cs, last ? 0 : tap + 1, wB);  // one reduction tile ahead (clamped at the very end)
+            load_w(ncs_, ntap, wn);  // one reduction tile ahead
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
@@ -238,7 +237,7 @@ __global__ __launch_bounds__(NT, 3) void conv_tile64_kernel(const T64Args a) {
                         smem + frow[j] + (ks < 3 ? tapoff + (ks + 1) * 32 : tapoff1));
 #pragma unroll
                 for (int j = 0; j < FM; ++j)
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wA[ks], fa[ks & 1][j], acc[j], 0, 0, 0);
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[ks], fa[ks & 1][j], acc[j], 0, 0, 0);
             }
             // issue order: the 4 weight loads ride on the first MFMAs, then one fragment read per MFMA
 #pragma unroll
@@ -253,10 +252,38 @@ __global__ __launch_bounds__(NT, 3) void conv_tile64_kernel(const T64Args a) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
+        };
+        if constexpr (T9) {
+            constexpr int RWc = TW + 2;
+            auto off = [](int t) { return ((t / 3) * RWc + (t % 3)) * PITCH; };
+            // taps 0, 2, 4, 6, 8 run from wA and fetch into wB, the odd ones the other way round; the weights of the
+            // next slice's first tap arrive in wB and are moved once per slice (after the last tap the fragment read
+            // is discarded, and past the last slice the weight load is a harmless repeat)
+            tap_body(wA, wB, off(0), off(1), cs, 1);
+            tap_body(wB, wA, off(1), off(2), cs, 2);
+            tap_body(wA, wB, off(2), off(3), cs, 3);
+            tap_body(wB, wA, off(3), off(4), cs, 4);
+            tap_body(wA, wB, off(4), off(5), cs, 5);
+            tap_body(wB, wA, off(5), off(6), cs, 6);
+            tap_body(wA, wB, off(6), off(7), cs, 7);
+            tap_body(wB, wA, off(7), off(8), cs, 8);
+            tap_body(wA, wB, off(8), off(8), cs1, 0);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) wA[ks] = wB[ks];
-            r = r1;
-            s = s1;
+        } else {
+            int r = 0, s = 0;
+            for (int tap = 0; tap < RS; ++tap) {
+                const bool last = tap + 1 == RS;
+                int s1 = s + 1, r1 = r;
+                if (s1 == g.S) { s1 = 0; r1 = r + 1; }
+                const int tapoff = (r * a.RW + s) * PITCH;
+                const int tapoff1 = last ? tapoff : (r1 * a.RW + s1) * PITCH;  // after the last tap the read is discarded
+                tap_body(wA, wB, tapoff, tapoff1, last ? cs1 : cs, last ? 0 : tap + 1);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) wA[ks] = wB[ks];
+                r = r1;
+                s = s1;
+            }
         }
         __builtin_amdgcn_s_setprio(0);
     }
@@ -292,6 +319,7 @@ __global__ __launch_bounds__(NT, 3) void conv_tile64_kernel(const T64Args a) {
     }
     __syncthreads();
     float csum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // column sums over this thread's rows (its 8 channels)
+    if (a.out || a.colsum)  // (pooled output only: nothing to store per pixel)
     for (int row = tid / VPR; row < BM; row += RPP) {
         const int m = (img * g.OH + oh0 + row / TW) * g.OW + ow0 + row % TW;
         u32x4 vv = *reinterpret_cast<const u32x4*>(smem + row * OPITCH + (tid % VPR) * 16);
@@ -355,9 +383,9 @@ __global__ __launch_bounds__(NT, 3) void conv_tile64_kernel(const T64Args a) {
     }
 }
 
-template <int TW, bool UP>
+template <int TW, bool UP, bool T9>
 int launch_t64(const T64Args& ta, hipStream_t st) {
-    auto kfn = conv_tile64_kernel<TW, UP>;
+    auto kfn = conv_tile64_kernel<TW, UP, T9>;
     constexpr size_t smem = (size_t)MAX_PATCH * PITCH;
     static std::atomic<bool> attr_done{false};
     if (!attr_done) {
@@ -386,11 +414,13 @@ int tile64_width(const GemmGeom& g) {
 }
 
 const char* tile64_kernel_name(const GemmGeom& g, bool unpool) {
-    static const char* names[2][3] = {
-        {"conv_tile64_kernel<32,false>", "conv_tile64_kernel<16,false>", "conv_tile64_kernel<8,false>"},
-        {"conv_tile64_kernel<32,true>", "conv_tile64_kernel<16,true>", "conv_tile64_kernel<8,true>"}};
+    static const char* names[2][2][3] = {
+        {{"conv_tile64_kernel<32,false,false>", "conv_tile64_kernel<16,false,false>", "conv_tile64_kernel<8,false,false>"},
+         {"conv_tile64_kernel<32,true,false>", "conv_tile64_kernel<16,true,false>", "conv_tile64_kernel<8,true,false>"}},
+        {{"conv_tile64_kernel<32,false,true>", "conv_tile64_kernel<16,false,true>", "conv_tile64_kernel<8,false,true>"},
+         {"conv_tile64_kernel<32,true,true>", "conv_tile64_kernel<16,true,true>", "conv_tile64_kernel<8,true,true>"}}};
     const int tw = tile64_width(g);
-    return names[unpool ? 1 : 0][tw == 32 ? 0 : tw == 16 ? 1 : 2];
+    return names[g.R == 3 && g.S == 3 ? 1 : 0][unpool ? 1 : 0][tw == 32 ? 0 : tw == 16 ? 1 : 2];
 }
 
 // can the patch loader take the input operand pooled (2x2 / stride 2, whole windows) plus the argmax?
@@ -436,14 +466,15 @@ int launch_tile64(const GemmGeom& g, const bf16_t* A, const void* Wp, const floa
     ta.dTimg = make_fastdiv((uint32_t)ta.tiles_img);
     ta.dTx = make_fastdiv((uint32_t)ta.tiles_x);
     ta.dRW = make_fastdiv((uint32_t)ta.RW);
+    const bool t9 = g.R == 3 && g.S == 3;
     if (unpool_am) {
-        if (tw == 32) return launch_t64<32, true>(ta, st);
-        if (tw == 16) return launch_t64<16, true>(ta, st);
-        return launch_t64<8, true>(ta, st);
+        if (tw == 32) return t9 ? launch_t64<32, true, true>(ta, st) : launch_t64<32, true, false>(ta, st);
+        if (tw == 16) return t9 ? launch_t64<16, true, true>(ta, st) : launch_t64<16, true, false>(ta, st);
+        return t9 ? launch_t64<8, true, true>(ta, st) : launch_t64<8, true, false>(ta, st);
     }
-    if (tw == 32) return launch_t64<32, false>(ta, st);
-    if (tw == 16) return launch_t64<16, false>(ta, st);
-    return launch_t64<8, false>(ta, st);
+    if (tw == 32) return t9 ? launch_t64<32, false, true>(ta, st) : launch_t64<32, false, false>(ta, st);
+    if (tw == 16) return t9 ? launch_t64<16, false, true>(ta, st) : launch_t64<16, false, false>(ta, st);
+    return t9 ? launch_t64<8, false, true>(ta, st) : launch_t64<8, false, false>(ta, st);
 }
 
 }  // namespace wap
