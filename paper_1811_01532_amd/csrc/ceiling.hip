@@ -12,7 +12,7 @@
 // carries the average clock the loop ran at.
 #include "wap_internal.h"
 
-using namespace wap;
+namespace wap {
 
 namespace {
 
@@ -78,6 +78,10 @@ __global__ __launch_bounds__(kWaves * 64, 2) void ceiling_kernel(float* out, con
 }
 
 }  // namespace
+
+}  // namespace wap
+
+using namespace wap;
 
 extern "C" {
 
