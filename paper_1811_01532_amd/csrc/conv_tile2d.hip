@@ -743,10 +743,17 @@ bool tile2d_preferred(const GemmGeom& g) {
     const TileCfg c = tile_cfg(g);
     if (c.variant == 0) return g.Ncols <= 128;
     if (c.variant == 3) {  // measured against the generic tap-by-tap kernel (64 channels) and conv_patch (wider)
+        // 192 output channels on 13 x 13 maps (384 -> 192 data gradient): 27 against 38 us at minibatch 32 (87 tiles), 27
+        // against 41 us at 64; at 16 and below (45 tiles and fewer) the generic kernel with a split reduction wins
         const long t3 = (long)((g.M + 191) / 192) * (g.Ncols / 64);
-        return g.Ncols == 64 ? t3 >= 48 : (t3 >= 200 || flat64_wins_small_batch(g));
+        return g.Ncols == 64 ? t3 >= 48 : (t3 >= 80 || flat64_wins_small_batch(g));
     }
-    return (long)((g.M + tile_pixels(c) - 1) / tile_pixels(c)) * (g.Ncols / 128) >= kNumCU * 3 / 4;
+    const long wgs = (long)((g.M + tile_pixels(c) - 1) / tile_pixels(c)) * (g.Ncols / 128);
+    // 64-pixel flat tiles keep winning against the generic kernel well below a work-group per CU while the reduction is
+    // short (13 x 13 layers of 192 .. 384 input channels at minibatch 8 .. 32: 23 against 36 us, 18 against 26 us, 17
+    // against 21 us); with 512 input channels (reduction 4608) the generic kernel's split reduction draws level
+    if (c.variant == 2 && c.fm == 2 && wgs >= 64 && g.Kred <= 3456) return true;
+    return wgs >= kNumCU * 3 / 4;
 }
 
 const char* tile2d_kernel_name(const GemmGeom& g, bool unpool) {
