@@ -295,27 +295,38 @@ __global__ __launch_bounds__(NT, 3) void conv_tile64_kernel(const T64Args a) {
     constexpr int RPP = NT / VPR;        // pixel rows stored per pass
     static_assert(BM * OPITCH <= MAX_PATCH * PITCH, "the staged tile must fit the patch area");
     __syncthreads();  // the last readers of the patch are done
+    // bias and ReLU are decided once for the whole tile (four straight-line variants), not per register group
+    auto stage_tile = [&](auto bias_tag, auto relu_tag) {
+        constexpr bool BIAS = decltype(bias_tag)::value, RELU = decltype(relu_tag)::value;
 #pragma unroll
-    for (int j = 0; j < FM; ++j) {
-        const int srow = (pg * FM + j) * 32 + (lane & 31);
+        for (int j = 0; j < FM; ++j) {
+            const int srow = (pg * FM + j) * 32 + (lane & 31);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int nl = cg * 32 + q * 8 + (lane >> 5) * 4;  // channel
-            float v[4];
+            for (int q = 0; q < 4; ++q) {
+                const int nl = cg * 32 + q * 8 + (lane >> 5) * 4;  // channel
+                float v[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = acc[j][q * 4 + e];
-            if (a.bias) {
+                for (int e = 0; e < 4; ++e) v[e] = acc[j][q * 4 + e];
+                if (BIAS) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] += a.bias[nl + e];
+                    for (int e = 0; e < 4; ++e) v[e] += a.bias[nl + e];
+                }
+                if (RELU) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+                }
+                uint2 pk = make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16),
+                                      (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+                *reinterpret_cast<uint2*>(smem + srow * OPITCH + nl * 2) = pk;
             }
-            if (a.relu) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
-            }
-            uint2 pk = make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16),
-                                  (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
-            *reinterpret_cast<uint2*>(smem + srow * OPITCH + nl * 2) = pk;
         }
+    };
+    if (a.bias) {
+        if (a.relu) stage_tile(std::true_type{}, std::true_type{});
+        else stage_tile(std::true_type{}, std::false_type{});
+    } else {
+        if (a.relu) stage_tile(std::false_type{}, std::true_type{});
+        else stage_tile(std::false_type{}, std::false_type{});
     }
     __syncthreads();
     float csum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // column sums over this thread's rows (its 8 channels)
