@@ -38,6 +38,10 @@ struct C3Args {
     // general filter (conv_c3_fwd_general_kernel): R x S taps, strides, reduction length R*S*3 in 16-deep steps
     int R, S, sh, sw, Kred, ksteps;
     FastDiv dS3;  // division by S * 3 (elements of one filter row)
+    // rows-in-LDS 3x3 forward (conv_c3_fwd_rows_kernel): 32-pixel tiles per output row, tiles in all
+    int tiles_row, ntiles;
+    unsigned x_bytes;
+    FastDiv dTR, dOH;
 };
 
 __device__ __align__(16) unsigned int g_zero_block_c3[4] = {0u, 0u, 0u, 0u};
@@ -54,7 +58,7 @@ __device__ __forceinline__ bf16x8 pack8(const unsigned short* h) {
 
 // FB: 32-channel blocks of output channels (K = 32 * FB)
 template <int FB>
-__global__ __launch_bounds__(NT) void conv_c3_fwd_kernel(const C3Args a) {
+__global__ __launch_bounds__(NT, 4) void conv_c3_fwd_kernel(const C3Args a) {
     constexpr int K = 32 * FB;
     constexpr int OPITCH = K * 2 + 16;
     __shared__ __align__(16) unsigned char stage[4][32 * OPITCH];
@@ -145,13 +149,148 @@ __global__ __launch_bounds__(NT) void conv_c3_fwd_kernel(const C3Args a) {
     }
 }
 
+// The same product on maps whose output rows are whole 32-pixel tiles and whose input rows hold an even number of
+// pixels (VGG's 224 x 224): instead of gathering its 16 x-elements one by one (an address computation and a bounds
+// check each, ~200 vector instructions per tile, which kept this kernel a third below the rate its output stream
+// allows), a wavefront stages the three input rows of its tile -- 36 pixels x 3 channels each, ONE 4-byte load per
+// lane and row, starting at an even pixel so that every load is aligned and lies wholly inside or outside the image --
+// in a wavefront-private LDS strip, and builds the fragments from there with sixteen 2-byte reads whose addresses
+// are computed once per kernel.
+template <int FB>
+__global__ __launch_bounds__(NT, 4) void conv_c3_fwd_rows_kernel(const C3Args a) {
+    constexpr int K = 32 * FB;
+    constexpr int OPITCH = K * 2 + 16;
+    constexpr int XROW = 256;  // bytes per staged input row: one dword per lane (216 bytes used)
+    constexpr unsigned OOB = 0x80000000u;  // x is below 2 GiB (checked on the host)
+    __shared__ __align__(16) unsigned char stage[4][32 * OPITCH];
+    __shared__ __align__(16) unsigned char xin[4][3 * XROW];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const bf16_t* zero_src = reinterpret_cast<const bf16_t*>(g_zero_block_c3);
+    const __amdgpu_buffer_rsrc_t rsrcX =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a.x), 0, (int)a.x_bytes, 0x00020000);
+
+    bf16x8 wf[FB][2];
+#pragma unroll
+    for (int b = 0; b < FB; ++b)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            unsigned short h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = ks * 16 + half * 8 + e;
+                h[e] = *(k < 27 ? a.w + (b * 32 + l32) * 27 + k : zero_src);
+            }
+            wf[b][ks] = pack8(h);
+        }
+
+    // the staged rows start at pixel ow0 - pad_w - adj, which is even (ow0 is a multiple of 32): element k = r * 9 + j of
+    // this lane's pixel l32 sits at byte r * XROW + ((l32 + adj) * 3 + j) * 2 of the strip; k >= 27 (the zero padding of
+    // the reduction) reads the tail of a staged row, which lanes 54 .. 63 fill with the zeros of their masked loads
+    const int adj = a.pad_w & 1;
+    unsigned char* xs = xin[wave];
+    const unsigned char* xrd[2][8];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = ks * 16 + half * 8 + e;
+            const int r = (k * 57) >> 9, j = k - r * 9;  // k / 9, k % 9 for k < 32
+            xrd[ks][e] = k < 27 ? xs + r * XROW + ((l32 + adj) * 3 + j) * 2 : xs + 216;  // bytes 216 .. 255 of a row: always zero
+        }
+    // the two bf16 elements of this lane's dword belong to the staged pixels (2 lane) / 3 and (2 lane + 1) / 3
+    const int dp0 = (2 * lane) / 3, dp1 = (2 * lane + 1) / 3;
+
+    unsigned char* st = stage[wave];
+    for (int tile = blockIdx.x * 4 + wave; tile < a.ntiles; tile += gridDim.x * 4) {
+        const int rowi = (int)fdiv((uint32_t)tile, a.dTR);        // (image, output row)
+        const int ow0 = (tile - rowi * a.tiles_row) * 32;
+        const int n = (int)fdiv((uint32_t)rowi, a.dOH);
+        const int oh = rowi - n * a.OH;
+        const int iws = ow0 - a.pad_w - adj;
+        const bool colok = lane < 54 && (unsigned)(iws + dp0) < (unsigned)a.W && (unsigned)(iws + dp1) < (unsigned)a.W;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int ih = oh - a.pad_h + r;
+            const bool ok = colok && (unsigned)ih < (unsigned)a.H;
+            const unsigned off = (unsigned)((((n * a.H + ih) * a.W + iws) * 3 + 2 * lane) * 2);
+            const unsigned v = __builtin_amdgcn_raw_buffer_load_b32(rsrcX, ok ? off : OOB, 0, 0);
+            *reinterpret_cast<unsigned*>(xs + r * XROW + lane * 4) = v;
+        }
+        // the strip is written as dwords and read as halfwords: keep the compiler from moving the reads in front of the
+        // writes (the LDS pipe itself executes a wavefront's operations in order, so no wait is needed)
+        asm volatile("" ::: "memory");
+        bf16x8 xf[2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            unsigned short h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                h[e] = *reinterpret_cast<const unsigned short*>(xrd[ks][e]);
+            }
+            xf[ks] = pack8(h);
+        }
+        f32x16 acc[FB];
+#pragma unroll
+        for (int b = 0; b < FB; ++b) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][ks], xf[ks], acc[b], 0, 0, 0);
+        }
+        // accumulator register i of block b: channel b*32 + (i/4)*8 + half*4 + i%4 of pixel l32; bias and ReLU are
+        // decided once per tile (four straight-line variants)
+        auto stage_tile = [&](auto bias_tag, auto relu_tag) {
+            constexpr bool BIAS = decltype(bias_tag)::value, RELU = decltype(relu_tag)::value;
+#pragma unroll
+            for (int b = 0; b < FB; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int ch = b * 32 + q * 8 + half * 4;
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = acc[b][q * 4 + e];
+                    if (BIAS) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += a.bias[ch + e];
+                    }
+                    if (RELU) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+                    }
+                    *reinterpret_cast<uint2*>(st + l32 * OPITCH + ch * 2) =
+                        make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16),
+                                   (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+                }
+        };
+        if (a.bias) {
+            if (a.relu) stage_tile(std::true_type{}, std::true_type{});
+            else stage_tile(std::true_type{}, std::false_type{});
+        } else {
+            if (a.relu) stage_tile(std::false_type{}, std::true_type{});
+            else stage_tile(std::false_type{}, std::false_type{});
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the strips are private to this wavefront
+        constexpr int VPR = K / 8;  // 16-byte vectors per pixel
+        const size_t m0 = ((size_t)rowi * a.OW + ow0);
+#pragma unroll
+        for (int it = 0; it < 32 * VPR / 64; ++it) {
+            const int v = it * 64 + lane;
+            const int px = v / VPR, vec = v % VPR;
+            u32x4 val = *reinterpret_cast<const u32x4*>(st + px * OPITCH + vec * 16);
+            *reinterpret_cast<u32x4*>(a.y + (m0 + px) * K + vec * 8) = val;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // strip reads done before the next tile overwrites them
+    }
+}
+
 // Any filter size and stride (e.g. 11x11 stride 4): the weights do not fit in registers any more (Kred = R*S*3 up
 // to a few hundred), so every work-group packs them once into MFMA fragment order in LDS,
 // [reduction step][channel block][lane][8], and its wavefronts walk 32-pixel tiles persistently; the x fragment of a
 // step is gathered element-wise exactly as above (k = r * (3 S) + j addresses element (ow*sw - pad)*3 + j of input
 // row oh*sh - pad + r).
 template <int FB>
-__global__ __launch_bounds__(NT) void conv_c3_fwd_general_kernel(const C3Args a) {
+__global__ __launch_bounds__(NT, 2) void conv_c3_fwd_general_kernel(const C3Args a) {
     constexpr int K = 32 * FB;
     constexpr int OPITCH = K * 2 + 16;
     extern __shared__ __align__(16) unsigned char dyn[];
@@ -251,7 +390,7 @@ __device__ __forceinline__ bf16x8 tr_pair(const unsigned char* p0, const unsigne
 
 // dw[ko][k] partial sums; requires OW % 8 == 0 (an 8-pixel run never leaves its image row)
 template <int FB>
-__global__ __launch_bounds__(NT) void wgrad_c3_kernel(const C3Args a) {
+__global__ __launch_bounds__(NT, 3) void wgrad_c3_kernel(const C3Args a) {
     constexpr int K = 32 * FB;
     constexpr int DPITCH = K * 2 + 64;  // transposing reads: 4 rows x 64 bytes in disjoint bank groups
     constexpr int VPR = K / 8;
@@ -358,7 +497,7 @@ struct C3SArgs {
 };
 
 template <int FB>
-__global__ __launch_bounds__(NT) void wgrad_c3_strided_kernel(const C3SArgs a) {
+__global__ __launch_bounds__(NT, 2) void wgrad_c3_strided_kernel(const C3SArgs a) {
     constexpr int K = 32 * FB;
     constexpr int DPITCH = K * 2 + 64;
     constexpr int VPR = K / 8;
@@ -498,7 +637,7 @@ struct C3FArgs {
 constexpr int C3F_KS = 28;  // most reduction steps (weight fragments held in registers)
 
 template <int FB>
-__global__ __launch_bounds__(NT) void conv_c3_fwd_strided_kernel(const C3FArgs a) {
+__global__ __launch_bounds__(NT, 2) void conv_c3_fwd_strided_kernel(const C3FArgs a) {
     constexpr int K = 32 * FB;
     constexpr int OPITCH = K * 2 + 16;
     constexpr int VPR = K / 8;
@@ -676,6 +815,11 @@ int c3_grid(long units) {
 
 namespace {
 bool c3_special(const GemmGeom& g) { return g.R == 3 && g.S == 3 && g.mul_h == 1 && g.mul_w == 1; }
+// 3x3 stride 1 with whole 32-pixel tiles per output row and 4-byte-aligned input rows: input rows staged in LDS
+bool c3_rows(const GemmGeom& g) {
+    return c3_special(g) && (g.OW % 32) == 0 && (g.IW % 2) == 0 &&
+           (double)(g.M / ((long)g.OH * g.OW)) * g.IH * g.IW * 3 * 2.0 < 2147483648.0;
+}
 size_t c3_general_smem(const GemmGeom& g) {
     const size_t ksteps = (size_t)(g.Kred + 15) / 16;
     return 4 * 32 * (size_t)(g.Ncols * 2 + 16) + ksteps * (g.Ncols / 32) * 64 * 16;
@@ -687,6 +831,7 @@ bool conv_c3_fwd_supported(const GemmGeom& g) {
     return c3_special(g) || c3_fwd_strided(g) || c3_general_smem(g) <= 64 * 1024;
 }
 const char* conv_c3_fwd_kernel_name(const GemmGeom& g) {
+    if (c3_rows(g)) return g.Ncols == 64 ? "conv_c3_fwd_rows_kernel<2>" : "conv_c3_fwd_rows_kernel<1>";
     if (c3_special(g)) return g.Ncols == 64 ? "conv_c3_fwd_kernel<2>" : "conv_c3_fwd_kernel<1>";
     if (c3_fwd_strided(g)) return g.Ncols == 64 ? "conv_c3_fwd_strided_kernel<2>" : "conv_c3_fwd_strided_kernel<1>";
     return g.Ncols == 64 ? "conv_c3_fwd_general_kernel<2>" : "conv_c3_fwd_general_kernel<1>";
@@ -759,6 +904,16 @@ int launch_conv_c3_fwd(const GemmGeom& g, const bf16_t* x, const bf16_t* w, cons
         if (g.Ncols == 64) hipLaunchKernelGGL(conv_c3_fwd_general_kernel<2>, dim3(ggrid), dim3(NT), smem, st, a);
         else hipLaunchKernelGGL(conv_c3_fwd_general_kernel<1>, dim3(ggrid), dim3(NT), smem, st, a);
         return check_launch("conv_c3_fwd_general");
+    }
+    if (c3_rows(g)) {
+        a.tiles_row = g.OW / 32;
+        a.ntiles = (g.M / g.OW) * a.tiles_row;
+        a.x_bytes = (unsigned)((size_t)a.N * g.IH * g.IW * 3 * 2);
+        a.dTR = make_fastdiv((uint32_t)a.tiles_row);
+        a.dOH = make_fastdiv((uint32_t)g.OH);
+        if (g.Ncols == 64) hipLaunchKernelGGL(conv_c3_fwd_rows_kernel<2>, dim3(grid), dim3(NT), 0, st, a);
+        else hipLaunchKernelGGL(conv_c3_fwd_rows_kernel<1>, dim3(grid), dim3(NT), 0, st, a);
+        return check_launch("conv_c3_fwd_rows");
     }
     if (g.Ncols == 64) hipLaunchKernelGGL(conv_c3_fwd_kernel<2>, dim3(grid), dim3(NT), 0, st, a);
     else hipLaunchKernelGGL(conv_c3_fwd_kernel<1>, dim3(grid), dim3(NT), 0, st, a);

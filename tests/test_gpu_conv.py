@@ -71,6 +71,10 @@ CASES = [
     ("c3_k64_ragged", (3, 41, 40, 3, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("c3_k32", (2, 48, 48, 3, 32, 3, 3, 1, 1), (-1, -1, -1)),
     ("c3_k64_pad0", (2, 50, 50, 3, 64, 3, 3, 1, 0), (-1, -1, -1)),
+    # ... with whole 32-pixel tiles per output row and even input rows: input rows staged in LDS (pad 1, pad 0, pad 2)
+    ("c3_rows_k64_w64", (3, 21, 64, 3, 64, 3, 3, 1, 1), (-1, -1, -1)),
+    ("c3_rows_k32_w66_pad0", (2, 19, 66, 3, 32, 3, 3, 1, 0), (-1, -1, -1)),
+    ("c3_rows_k64_w94_pad2", (2, 12, 94, 3, 64, 3, 3, 1, 2), (-1, -1, -1)),
     ("c3_general_5x5_s2_k32", (9, 63, 61, 3, 32, 5, 5, 2, 2), (-1, -1, -1)),
     ("c3_general_11x11_s4_k64", (4, 131, 135, 3, 64, 11, 11, 4, 2), (-1, -1, -1)),
     ("c3_general_7x3_rect_stride_1_3", (3, 20, 40, 3, 64, 7, 3, (1, 3), (3, 0)), (-1, -1, -1)),
