@@ -9,7 +9,8 @@ extern "C" {
 #endif
 
 /* Process-wide and NOT thread safe (plain globals read while a plan is made): force the tile configuration of
- * the forward-type kernels (0..3), of the weight-gradient kernel (0..2) and the number of reduction splits;
+ * the forward-type kernels (0..9), of the weight-gradient kernel (0..4; 5 / 6: the patch kernel with two / one
+ * 32-channel dy blocks per wavefront) and the number of reduction splits;
  * -1 restores the shape-driven choice.  Forced values that the shape cannot use are ignored, and the
  * *_workspace_bytes queries reflect the forced choice.  Lets the tests reach every kernel and tile
  * configuration with small shapes. */

@@ -335,7 +335,9 @@ WgradPlan plan_wgrad(const WgradGeom& g) {
         p.ws_bytes = (size_t)p.nsplit * g.K * Kred * sizeof(float);  // always reduced from per-work-group partials
         return p;
     }
-    if ((g_force_wgrad_cfg < 0 || g_force_wgrad_cfg == 3) && mode == 0 && wgrad_patch_supported(g)) {
+    // (5 / 6: the patch kernel with two / one dy blocks per wavefront, for the tests)
+    if ((g_force_wgrad_cfg < 0 || g_force_wgrad_cfg == 3 || g_force_wgrad_cfg == 5 || g_force_wgrad_cfg == 6) && mode == 0 &&
+        wgrad_patch_supported(g)) {
         p.cfg = 3;
         p.nsplit = g_force_nsplit >= 1 ? g_force_nsplit : wgrad_patch_nsplit(g);
         long tiles_total = (long)g.N * g.P * g.Q / 64;  // every tile holds at least 64 pixels

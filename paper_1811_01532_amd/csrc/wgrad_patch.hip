@@ -357,15 +357,15 @@ struct TileShape {
     int nk() const { return TH * VW / 16; }
 };
 
-int fd_for(const WgradGeom& g) { return (g.K % 128) == 0 ? 2 : 1; }
+bool choose_tile_fd(const WgradGeom& g, int fd, struct TileShape* out);
+int fd_for(const WgradGeom& g);
 size_t buf_bytes_for(int fd, const TileShape& ts) {
     return (size_t)(ts.TH + 2) * (ts.VW + 2) * XPITCH + (size_t)ts.TH * ts.VW * (fd * 128 + 64);
 }
 
 // Most real pixels per tile (the tile height need not divide the map: the last tile row of an image is then partly
 // masked) among the tiles the kernel's three step maps cover and whose two LDS buffers fit; then the least padding.
-bool choose_tile(const WgradGeom& g, TileShape* out) {
-    const int fd = fd_for(g);
+bool choose_tile_fd(const WgradGeom& g, int fd, TileShape* out) {
     long best = 0;
     for (int twr = 1; twr <= g.Q && twr <= 32; ++twr) {
         if (g.Q % twr) continue;
@@ -388,6 +388,23 @@ bool choose_tile(const WgradGeom& g, TileShape* out) {
     }
     return best > 0;
 }
+
+// 32-channel dy blocks per wavefront: two where the layer has a multiple of 128 output channels, unless the pixel range
+// is short (at most 28 tiles per work-group: small minibatches, the 14 x 14 layers): the fp32 partial tiles that every
+// work-group writes and the reduction that reads them then weigh more than the better register tile saves, and
+// 64-channel work-groups halve those bytes for the same number of work-groups (conv4_2 at minibatch 8: 75 -> 38 MB).
+// Measured on whole steps with the limit at 8 / 16 / 28 tiles: VGG-16 -5.1 / -5.1 / -5.2 % at b = 8, -2.2 / -3.4 / -3.6 %
+// at 16, -0.9 / -1.0 / -1.3 % at 32, 0 / 0 / -0.5 % at 64; the AlexNet-style step -2 .. -3 % at b = 8 .. 64.
+int fd_for(const WgradGeom& g) {
+    if ((g.K % 128) != 0 || g_force_wgrad_cfg == 6) return 1;
+    if (g_force_wgrad_cfg == 5) return 2;
+    TileShape ts;
+    if (!choose_tile_fd(g, 2, &ts)) return 1;
+    const long tiles = (long)g.N * ((g.P + ts.TH - 1) / ts.TH) * (g.Q / ts.TWr);
+    const long ncombo2 = (long)(g.K / 128) * (g.C / 64);
+    return tiles * ncombo2 <= 28L * kNumCU ? 1 : 2;
+}
+bool choose_tile(const WgradGeom& g, TileShape* out) { return choose_tile_fd(g, fd_for(g), out); }
 
 }  // namespace
 

@@ -211,8 +211,10 @@ def test_wide_maps_leave_the_16bit_coordinate_kernel(wap):
 def test_patch_weight_gradient_tile_and_step_map_per_layer(wap):
     """Host-side plan of the patch weight-gradient kernel <FD, UP, step map, steps per tile>: block steps on the
     28-wide tiles of conv2_x .. conv4_x need no padded pixel, 14- and 13-wide maps run 7-row tiles of width 16,
-    64-channel layers take one dy block per wavefront, and the pool backward is routed in the loader exactly where
-    tiles have even height; maps too small for a 7-row or 4-row tile fall to the generic kernel."""
+    64-channel layers take one dy block per wavefront, and so does any layer whose pixel range is short (at most 28
+    tiles per work-group: small minibatches, the 14 x 14 layers), where the fp32 partial tiles outweigh the register
+    tile; the pool backward is routed in the loader exactly where tiles have even height; maps too small for a 7-row
+    or 4-row tile fall to the generic kernel."""
     def name(N, H, W, C, K):
         return wap.wap_conv2d_kernel_name(wap.conv_desc(N, H, W, C, K, 3, 3, 1, 1), wap.WAP_PASS_BWD_WEIGHT)
 
@@ -220,10 +222,13 @@ def test_patch_weight_gradient_tile_and_step_map_per_layer(wap):
         return wap.wap_conv2d_bwd_pool2x2_fused(wap.conv_desc(N, H, W, C, K, 3, 3, 1, 1), wap.WAP_PASS_BWD_WEIGHT)
     assert name(64, 28, 28, 512, 512) == "wgrad_patch_kernel<2,false,2,7>" and fused(64, 28, 28, 512, 512)
     assert name(64, 56, 56, 256, 256) == "wgrad_patch_kernel<2,false,2,7>" and fused(64, 56, 56, 256, 256)
-    assert name(64, 14, 14, 512, 512) == "wgrad_patch_kernel<2,false,0,7>" and not fused(64, 14, 14, 512, 512)
+    assert name(64, 14, 14, 512, 512) == "wgrad_patch_kernel<1,false,0,7>" and not fused(64, 14, 14, 512, 512)
+    assert name(256, 14, 14, 512, 512) == "wgrad_patch_kernel<2,false,0,7>"
+    assert name(8, 28, 28, 512, 512) == "wgrad_patch_kernel<1,false,2,7>"
     assert name(64, 112, 112, 128, 128) == "wgrad_patch_kernel<2,false,0,8>" and fused(64, 112, 112, 128, 128)
     assert name(64, 224, 224, 64, 64) == "wgrad_patch_kernel<1,false,0,8>" and fused(64, 224, 224, 64, 64)
-    assert name(32, 13, 13, 384, 256) == "wgrad_patch_kernel<2,false,0,7>"
+    assert name(32, 13, 13, 384, 256) == "wgrad_patch_kernel<1,false,0,7>"
+    assert name(512, 13, 13, 384, 256) == "wgrad_patch_kernel<2,false,0,7>"
     assert not name(8, 6, 12, 64, 128).startswith("wgrad_patch")     # no 7-row tile on a 6-row map
     assert not name(8, 3, 28, 64, 128).startswith("wgrad_patch")     # no 4-row tile on a 3-row map
 

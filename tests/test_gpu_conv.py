@@ -62,6 +62,15 @@ CASES = [
     ("wgrad_patch_blocks_w28_k64", (2, 28, 28, 64, 64, 3, 3, 1, 1), (-1, -1, -1)),
     ("wgrad_patch_halfrows_w32_k128", (2, 12, 32, 64, 128, 3, 3, 1, 1), (-1, -1, -1)),
     ("wgrad_patch_blocks_w20_k128_two_tiles_per_row", (1, 12, 40, 128, 128, 3, 3, 1, 1), (-1, -1, -1)),
+    # small shapes have short pixel ranges, for which the plan picks one 32-channel dy block per wavefront; the same
+    # shapes with two blocks forced (the arrangement of the large layers), every step map, with and without pooled dy
+    ("wgrad_patch_two_blocks_rows16_x8", (1, 8, 8, 256, 128, 3, 3, 1, 1), (-1, 5, -1)),
+    ("wgrad_patch_two_blocks_blocks_w22", (2, 88, 88, 64, 128, 3, 3, 1, 1), (-1, 5, -1)),
+    ("wgrad_patch_two_blocks_blocks_w28", (3, 28, 28, 128, 256, 3, 3, 1, 1), (7, 5, -1)),
+    ("wgrad_patch_two_blocks_rows16_x7_w14", (5, 14, 14, 64, 128, 3, 3, 1, 1), (7, 5, -1)),
+    ("wgrad_patch_two_blocks_halfrows_w32", (2, 12, 32, 64, 128, 3, 3, 1, 1), (-1, 5, -1)),
+    ("wgrad_patch_two_blocks_blocks_w20", (1, 12, 40, 128, 128, 3, 3, 1, 1), (-1, 5, -1)),
+    ("wgrad_patch_two_blocks_w13_masked_rows", (3, 13, 13, 192, 128, 3, 3, 1, 1), (-1, 5, -1)),
     # backward through a 2x2 pool routed in the loaders: flat data-gradient tiles, two dy blocks per wavefront
     ("unpool_flat_w14_c128_k128", (5, 14, 14, 128, 128, 3, 3, 1, 1), (7, -1, -1)),
     ("unpool_w112_c64_k128", (1, 32, 112, 64, 128, 3, 3, 1, 1), (-1, -1, -1)),
